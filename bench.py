@@ -1,0 +1,136 @@
+#!/usr/bin/env python3
+"""Benchmark of the padded sigmoid-attention hot path on one MI355X.
+
+A step is one pass of the whole hot path -- forward, then backward (dK/dV kernel, dQ kernel) -- over one
+batch of the seeded synthetic workload, inputs resident in HBM.  The metric is fwd+bwd TFLOPS over
+valid-token FLOPs (paper appendix "FLOP Calculation": forward 4 h d sum_z n_z^2, backward 2.5 x that),
+also given as a fraction of the MI355X dense bf16 MFMA peak.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload long] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense bf16 MFMA
+PAPER_CONTEXT = "paper: 515.6 TFLOPS fwd / 373.5 bwd on H100, d=128, N=16384, unpadded (another machine; context only)"
+
+
+def cpu_baseline(w, budget_s: float = 15.0):
+    """The fp64 oracle, as it stands, timed on the host cores over whole (z, h) slices of the shortest
+    sequence of this workload until about budget_s seconds have been spent."""
+    import oracle
+    z = int(np.argmin(np.where(w.seqlens > 0, w.seqlens, np.iinfo(np.int32).max)))
+    n = int(w.seqlens[z])
+    per_slice = 14 * w.d * n * n
+    done, t0 = 0, time.perf_counter()
+    for h in range(w.H):
+        oracle.fwd(w.q, w.k, w.v, w.seqlens, w.bias, w.scale, slices=[(z, h)])
+        oracle.bwd(w.q, w.k, w.v, w.d_o, w.seqlens, w.bias, w.scale, slices=[(z, h)])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done * per_slice / dt / 1e12, "unit": "TFLOPS", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"fwd+bwd of {done} (z,h) slice(s) of sequence z={z} (n={n}, d={w.d}) of workload "
+                      f"'{w.name}', {dt:.1f} s, fp64 plain loops",
+            "seconds": dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="long")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
+              "DESIGN.md says how the path would shard.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_27124_amd import binding
+    from paper_2604_27124_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    binding.load()
+
+    w = W.generate(args.workload, args.seed)
+    dev = lambda a: torch.from_numpy(W.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v, g = dev(w.q), dev(w.k), dev(w.v), dev(w.d_o)
+    seqlens = torch.from_numpy(w.seqlens).cuda()
+    bias = torch.from_numpy(w.bias).cuda()
+    o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev: ev[0].record(stream)
+        binding.sigmoid_attn_fwd(q, k, v, seqlens, bias, w.scale, out=o, stream=stream)
+        if ev: ev[1].record(stream)
+        binding.sigmoid_attn_bwd_dkdv(q, k, v, g, seqlens, bias, w.scale, dk=dk, dv=dv, stream=stream)
+        if ev: ev[2].record(stream)
+        binding.sigmoid_attn_bwd_dq(q, k, v, g, seqlens, bias, w.scale, dq=dq, stream=stream)
+        if ev: ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in events])   # fwd, dkdv, dq
+    mean_ms = ms.mean(axis=0)
+    pairs = int(np.sum(w.seqlens.astype(np.int64) ** 2))
+    f_fwd = 4 * w.H * w.d * pairs
+    f_bwd = 10 * w.H * w.d * pairs
+    ms_per_step = wall * 1e3 / args.steps
+    tflops = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the one with the largest share of the step
+    names = ["fwd", "bwd_dkdv", "bwd_dq"]
+    alg_flops = [f_fwd, 6 * w.H * w.d * pairs, 4 * w.H * w.d * pairs]    # contractions the pass must do: 2, 3(+S), 2(+S)
+    # algorithmic FLOPs of a launch = the counted FLOPs of the quantities it produces:
+    #   fwd: S, PV (4 d per pair); dK/dV kernel: dP, dV, dK (6 d per pair); dQ kernel: dQ (2 d) + its share
+    #   of the single counted recomputation of S (2 d), i.e. backward = 10 d per pair in total.
+    dom = int(np.argmax(mean_ms))
+    achieved = alg_flops[dom] / (mean_ms[dom] * 1e-3) / 1e12
+
+    out = {
+        "metric": "fwd+bwd TFLOPS (valid-token FLOPs) + % of bf16 MFMA peak, d=64 N=8192",
+        "value": round(tflops, 2), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} N_max={w.N} seed={w.seed}",
+                   "seqlens": [int(x) for x in w.seqlens], "qkv_std": w.meta["qkv_std"],
+                   "valid_flops_fwd": f_fwd, "valid_flops_bwd": f_bwd},
+        "pct_of_bf16_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "kernels_ms": {n: round(float(m), 4) for n, m in zip(names, mean_ms)},
+        "kernels_tflops": {"fwd": round(f_fwd / (mean_ms[0] * 1e-3) / 1e12, 1),
+                           "bwd": round(f_bwd / ((mean_ms[1] + mean_ms[2]) * 1e-3) / 1e12, 1)},
+        "roofline": {"bound": "mfma", "kernel": names[dom], "achieved": round(achieved, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None},
+        "context": PAPER_CONTEXT,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,151 @@
+// Host side of libsigattn: argument validation, kernel selection and launch behind the C ABI
+// declared in include/sigmoid_attn.h.  Validation happens before any HIP call.
+#include "sigattn_kernels.hpp"
+#include "sigmoid_attn.h"
+
+#include <cmath>
+
+using namespace sigattn;
+
+namespace {
+
+struct Shape {
+    int B, N, H, d;
+};
+
+int check_shape(int B, int N, int H, int d) {
+    if (B <= 0 || N <= 0 || H <= 0) return SIGATTN_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return SIGATTN_ERR_UNSUPPORTED_D;
+    if ((long long)B * H > 65535LL) return SIGATTN_ERR_TOO_LARGE;          // grid.y limit
+    if ((long long)B * N * H * d >= (1LL << 40)) return SIGATTN_ERR_TOO_LARGE;
+    return SIGATTN_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
+int launch(const Params &p, hipStream_t stream) {
+    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
+    const long long tiles = ((long long)p.N + C::BM - 1) / C::BM;
+    if (tiles > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;
+    dim3 grid((unsigned)tiles, (unsigned)(p.B * p.H), 1);
+    dim3 block(C::THREADS, 1, 1);
+    auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC>;
+    hipLaunchKernelGGL(kern, grid, block, C::LDS_BYTES, stream, p);
+    return hipGetLastError() == hipSuccess ? SIGATTN_OK : SIGATTN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sigmoid_attn_version(void) { return 100; }
+
+const char *sigmoid_attn_strerror(int code) {
+    switch (code) {
+        case SIGATTN_OK: return "success";
+        case SIGATTN_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive dimension or non-finite scale)";
+        case SIGATTN_ERR_UNSUPPORTED_D: return "unsupported head dimension (must be 64 or 128)";
+        case SIGATTN_ERR_MISALIGNED: return "tensor pointer is not 16-byte aligned";
+        case SIGATTN_ERR_WORKSPACE: return "workspace missing or too small";
+        case SIGATTN_ERR_LAUNCH: return "HIP kernel launch failed";
+        case SIGATTN_ERR_TOO_LARGE: return "problem too large for one launch";
+        default: return "unknown error code";
+    }
+}
+
+size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d) {
+    if (check_shape(B, N_max, H, d) != SIGATTN_OK) return 0;
+    return 0;   // the backward pass owns each output tile exclusively: no scratch, no atomics
+}
+
+int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
+                     const int32_t *seqlens, const float *bias, float scale,
+                     int B, int N_max, int H, int d, void *stream) {
+    if (!q || !k || !v || !o || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, N_max, H, d)) return e;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SIGATTN_ERR_MISALIGNED;
+
+    Params p{};
+    p.q = static_cast<const bf16_t *>(q);
+    p.k = static_cast<const bf16_t *>(k);
+    p.v = static_cast<const bf16_t *>(v);
+    p.d_o = nullptr;
+    p.out0 = static_cast<bf16_t *>(o);
+    p.out1 = nullptr;
+    p.seqlens = seqlens;
+    p.bias = bias;
+    p.scale = scale;
+    p.B = B; p.N = N_max; p.H = H;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d == 64) return launch<FWD, 64, 2, 4, 64, 72, 80, 2>(p, s);
+    return launch<FWD, 128, 1, 4, 64, 136, 144, 2>(p, s);
+}
+
+static int bwd_common(const void *q, const void *k, const void *v, const void *d_o,
+                      void *dq, void *dk, void *dv,
+                      const int32_t *seqlens, const float *bias, float scale,
+                      int B, int N_max, int H, int d, void *stream, bool want_dq, bool want_dkdv) {
+    if (!q || !k || !v || !d_o || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+    if ((want_dq && !dq) || (want_dkdv && (!dk || !dv))) return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, N_max, H, d)) return e;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o)) return SIGATTN_ERR_MISALIGNED;
+    if ((want_dq && !aligned16(dq)) || (want_dkdv && (!aligned16(dk) || !aligned16(dv))))
+        return SIGATTN_ERR_MISALIGNED;
+
+    Params p{};
+    p.q = static_cast<const bf16_t *>(q);
+    p.k = static_cast<const bf16_t *>(k);
+    p.v = static_cast<const bf16_t *>(v);
+    p.d_o = static_cast<const bf16_t *>(d_o);
+    p.seqlens = seqlens;
+    p.bias = bias;
+    p.scale = scale;
+    p.B = B; p.N = N_max; p.H = H;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (want_dkdv) {         // Alg. 3: dK, dV (owner = key tile)
+        Params pk = p;
+        pk.out0 = static_cast<bf16_t *>(dk);
+        pk.out1 = static_cast<bf16_t *>(dv);
+        const int e = (d == 64) ? launch<DKDV, 64, 1, 4, 64, 80, 80, 2>(pk, s)
+                                : launch<DKDV, 128, 1, 4, 64, 144, 144, 1>(pk, s);
+        if (e) return e;
+    }
+    if (want_dq) {           // Alg. 2: dQ (owner = query tile)
+        Params pq = p;
+        pq.out0 = static_cast<bf16_t *>(dq);
+        pq.out1 = nullptr;
+        const int e = (d == 64) ? launch<DQ, 64, 2, 4, 64, 80, 72, 2>(pq, s)
+                                : launch<DQ, 128, 1, 4, 64, 144, 136, 2>(pq, s);
+        if (e) return e;
+    }
+    return SIGATTN_OK;
+}
+
+int sigmoid_attn_bwd(const void *q, const void *k, const void *v, const void *d_o,
+                     void *dq, void *dk, void *dv,
+                     const int32_t *seqlens, const float *bias, float scale,
+                     int B, int N_max, int H, int d,
+                     void *workspace, size_t workspace_bytes, void *stream) {
+    if (!dq || !dk || !dv) return SIGATTN_ERR_INVALID_ARG;
+    const int e0 = bwd_common(q, k, v, d_o, dq, dk, dv, seqlens, bias, scale, B, N_max, H, d, nullptr, false, false);
+    if (e0) return e0;       // argument errors first, as the header orders them
+    const size_t need = sigmoid_attn_bwd_workspace_bytes(B, N_max, H, d);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return SIGATTN_ERR_WORKSPACE;
+    return bwd_common(q, k, v, d_o, dq, dk, dv, seqlens, bias, scale, B, N_max, H, d, stream, true, true);
+}
+
+int sigmoid_attn_bwd_dq(const void *q, const void *k, const void *v, const void *d_o, void *dq,
+                        const int32_t *seqlens, const float *bias, float scale,
+                        int B, int N_max, int H, int d, void *stream) {
+    return bwd_common(q, k, v, d_o, dq, nullptr, nullptr, seqlens, bias, scale, B, N_max, H, d, stream, true, false);
+}
+
+int sigmoid_attn_bwd_dkdv(const void *q, const void *k, const void *v, const void *d_o, void *dk, void *dv,
+                          const int32_t *seqlens, const float *bias, float scale,
+                          int B, int N_max, int H, int d, void *stream) {
+    return bwd_common(q, k, v, d_o, nullptr, dk, dv, seqlens, bias, scale, B, N_max, H, d, stream, false, true);
+}
+
+}  // extern "C"

@@ -1,0 +1,352 @@
+// Device code for padded bidirectional sigmoid attention on gfx950 (CDNA4).
+//
+// One kernel template serves the three passes of the method (paper appendix Alg. 1-3):
+//
+//   FWD   (Alg. 1): owner = a tile of queries,  streamed = key/value tiles.   Out = O
+//   DQ    (Alg. 2): owner = a tile of queries,  streamed = key/value tiles.   Out = dQ
+//   DKDV  (Alg. 3): owner = a tile of keys,     streamed = query/dO tiles.    Out = dK, dV
+//
+// "Owner" rows are held in registers for the whole kernel as MFMA B operands; "streamed" tiles go
+// HBM -> registers -> LDS (double buffered) and are read from LDS as MFMA A operands, either row-wise
+// (contraction over the head dimension) or through the transposing LDS read (contraction over tokens).
+// Every score tile is computed transposed, streamed x owner, so that the fp32 accumulator of one lane
+// holds one owner column and several streamed rows: after the fused sigmoid those registers are, without
+// any shuffle, the bf16 B operand of the next contraction over streamed tokens.
+//
+// v_mfma_f32_32x32x16_bf16 operand layout used below (lane l, c = l % 32, g = l / 32):
+//   A[32 x 16]: lane holds row c,    k = 8 g + 0..7
+//   B[16 x 32]: lane holds column c, k = 8 g + 0..7
+//   C[32 x 32]: lane holds column c, register i holds row 8 (i / 4) + 4 g + (i % 4)
+// ds_read_b64_tr_b16 within a group of 16 lanes: destination lane i, element e comes from the 8 bytes
+// addressed by lane (i / 4 + 4 e), 16-bit column (i % 4).  With lane r of the group pointing at
+// (row r / 4, column 4 (r % 4)) of a row-major [4 x 16] block, lane i receives column i, rows 0..3.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sigattn {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+enum Mode { FWD = 0, DQ = 1, DKDV = 2 };
+
+struct Params {
+    const bf16_t *q, *k, *v, *d_o;   // inputs  [B, N, H, D]
+    bf16_t *out0;                    // FWD: O;  DQ: dQ;  DKDV: dK
+    bf16_t *out1;                    // DKDV: dV
+    const int32_t *seqlens;          // [B]
+    const float *bias;               // [B]
+    float scale;
+    int B, N, H;
+};
+
+#define SIGATTN_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+__device__ __forceinline__ bf16x8 lds_read_rows(const bf16_t *p) {
+    return *reinterpret_cast<const bf16x8 *>(p);
+}
+
+// Two transposing reads -> the 8 contraction slots of one A operand.
+__device__ __forceinline__ bf16x8 lds_read_tr(const bf16_t *p_lo, const bf16_t *p_hi) {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SIGATTN_LDS_PTR(s16x4, p_lo));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SIGATTN_LDS_PTR(s16x4, p_hi));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
+    return __builtin_bit_cast(unsigned, h);
+}
+
+// Registers 8 half .. 8 half + 7 of a score accumulator -> bf16 B operand (contraction slots = streamed rows).
+__device__ __forceinline__ bf16x8 acc_to_operand(const f32x16 &a, int half) {
+    u32x4 r;
+    r[0] = pack_bf16(a[8 * half + 0], a[8 * half + 1]);
+    r[1] = pack_bf16(a[8 * half + 2], a[8 * half + 3]);
+    r[2] = pack_bf16(a[8 * half + 4], a[8 * half + 5]);
+    r[3] = pack_bf16(a[8 * half + 6], a[8 * half + 7]);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2>
+struct Cfg {
+    static constexpr int BM = NW * 32 * QB;        // owner rows per workgroup
+    static constexpr int THREADS = NW * 64;
+    static constexpr int KS = D / 16;              // MFMA steps over the head dimension
+    static constexpr int MB = D / 32;              // 32-row blocks of a transposed [D x 32] output
+    static constexpr int NB = BN / 32;             // 32-row blocks of a streamed tile
+    static constexpr int CH = D / 8;               // 16-byte chunks per row
+    static constexpr int PER = (BN * CH) / THREADS;  // chunks per thread per streamed tensor
+    static constexpr size_t LDS_BYTES = 2u * BN * (LD1 + LD2) * sizeof(bf16_t);
+    static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
+    static_assert(D % 32 == 0 && BN % 32 == 0, "tile shape");
+    static_assert(LD1 % 8 == 0 && LD2 % 8 == 0 && LD1 >= D && LD2 >= D, "LDS row stride");
+};
+
+// Write zeros over owner rows [row0, row1) of one (z, h) slice of `out`.
+template <int D, int THREADS>
+__device__ __forceinline__ void zero_rows(bf16_t *out, size_t slice_base, size_t row_stride, int row0, int row1) {
+    constexpr int CH = D / 8;
+    const int total = (row1 - row0) * CH;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int c = threadIdx.x; c < total; c += THREADS) {
+        const int r = row0 + c / CH;
+        *reinterpret_cast<u32x4 *>(out + slice_base + (size_t)r * row_stride + (size_t)(c % CH) * 8) = z;
+    }
+}
+
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
+__global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
+    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
+    constexpr bool HAS2 = (MODE != FWD);             // a second owner tensor and a second score tile (dP)
+    constexpr float LOG2E = 1.4426950408889634f;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *y1s = reinterpret_cast<bf16_t *>(smem);                 // [2][BN][LD1]
+    bf16_t *y2s = y1s + 2 * BN * LD1;                               // [2][BN][LD2]
+
+    const int zh = blockIdx.y;
+    const int z = zh / p.H, h = zh - z * p.H;
+    int n = p.seqlens[z];
+    n = n < 0 ? 0 : (n > p.N ? p.N : n);
+    const int m0 = blockIdx.x * C::BM;                              // first owner row of this workgroup
+    const int m1 = (m0 + C::BM < p.N) ? m0 + C::BM : p.N;
+    const size_t row_stride = (size_t)p.H * D;
+    const size_t slice = ((size_t)z * p.N * p.H + h) * D;           // element offset of row 0 of (z, h)
+
+    if (m0 >= n) {   // wholly padded owner tile: write zeros, do nothing else (block-sparse early exit)
+        zero_rows<D, C::THREADS>(p.out0, slice, row_stride, m0, m1);
+        if (MODE == DKDV) zero_rows<D, C::THREADS>(p.out1, slice, row_stride, m0, m1);
+        return;
+    }
+
+    const bf16_t *x1 = (MODE == DKDV) ? p.k : p.q;                  // owner tensors
+    const bf16_t *x2 = (MODE == DKDV) ? p.v : p.d_o;
+    const bf16_t *y1 = (MODE == DKDV) ? p.q : p.k;                  // streamed tensors
+    const bf16_t *y2 = (MODE == DKDV) ? p.d_o : p.v;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 31, g = lane >> 5;
+    const int wrow0 = m0 + wave * 32 * QB;                          // first owner row of this wave
+
+    // ---- owner rows -> registers (B operands): lane holds row c of each 32-block, d = 16 ks + 8 g + 0..7
+    bf16x8 xa[QB][C::KS];
+    bf16x8 xb[HAS2 ? QB : 1][HAS2 ? C::KS : 1];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int r = wrow0 + 32 * qb + c;
+        const bool ok = r < n;
+        const size_t off = slice + (size_t)(ok ? r : 0) * row_stride + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            u32x4 t = {0u, 0u, 0u, 0u};
+            if (ok) t = *reinterpret_cast<const u32x4 *>(x1 + off + 16 * ks);
+            xa[qb][ks] = __builtin_bit_cast(bf16x8, t);
+            if (HAS2) {
+                u32x4 t2 = {0u, 0u, 0u, 0u};
+                if (ok) t2 = *reinterpret_cast<const u32x4 *>(x2 + off + 16 * ks);
+                xb[qb][ks] = __builtin_bit_cast(bf16x8, t2);
+            }
+        }
+    }
+
+    // sigma(x) = 1 / (1 + 2^t),  t = -(scale * log2 e) * s - bias * log2 e
+    const float c1 = -p.scale * LOG2E;
+    const float c0 = -p.bias[z] * LOG2E;
+
+    f32x16 acc0[QB][C::MB];                        // FWD: O^T;  DQ: dQ^T;  DKDV: dK^T
+    f32x16 acc1[MODE == DKDV ? QB : 1][MODE == DKDV ? C::MB : 1];   // DKDV: dV^T
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc0[qb][mb][i] = 0.f;
+            if (MODE == DKDV) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc1[qb][mb][i] = 0.f;
+            }
+        }
+
+    // ---- streamed tile movement: HBM -> registers -> LDS
+    const int ntiles = (n + BN - 1) / BN;
+    u32x4 st1[C::PER], st2[C::PER];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) {
+            const int cid = tid + it * C::THREADS;
+            const int r = t * BN + cid / C::CH;
+            const int col = (cid % C::CH) * 8;
+            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+            if (r < n) {    // rows beyond the valid length are filled with zeros, never read
+                const size_t off = slice + (size_t)r * row_stride + col;
+                a = *reinterpret_cast<const u32x4 *>(y1 + off);
+                b = *reinterpret_cast<const u32x4 *>(y2 + off);
+            }
+            st1[it] = a;
+            st2[it] = b;
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) {
+            const int cid = tid + it * C::THREADS;
+            const int r = cid / C::CH;
+            const int col = (cid % C::CH) * 8;
+            *reinterpret_cast<u32x4 *>(y1s + (buf * BN + r) * LD1 + col) = st1[it];
+            *reinterpret_cast<u32x4 *>(y2s + (buf * BN + r) * LD2 + col) = st2[it];
+        }
+    };
+
+    // lane-constant pieces of the LDS addresses
+    const int rd_row = c;                          // row-wise A operand: row c, columns 16 ks + 8 g
+    const int rd_col = 8 * g;
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1;
+    const int tr_row = 4 * g + (i16 >> 2);         // transposed A operand: rows 4 g + 0..3 (and + 8)
+    const int tr_col = 16 * g16 + 4 * (i16 & 3);   // 16 output rows (head-dim columns) per 16-lane group
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_tile(t + 1);
+        const bf16_t *t1 = y1s + buf * BN * LD1;
+        const bf16_t *t2 = y2s + buf * BN * LD2;
+        const bool partial = (t + 1) * BN > n;      // uniform: only the last tile can hold padded rows
+
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) {
+            // ---- transposed scores: S^T[streamed 32 x owner 32] = Y1 X1^T, and dP^T = Y2 X2^T
+            f32x16 s[QB];
+            f32x16 dp[HAS2 ? QB : 1];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[qb][i] = 0.f;
+                if (HAS2) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dp[qb][i] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) {
+                const bf16x8 a1 = lds_read_rows(t1 + (nb * 32 + rd_row) * LD1 + 16 * ks + rd_col);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], s[qb], 0, 0, 0);
+                if (HAS2) {
+                    const bf16x8 a2 = lds_read_rows(t2 + (nb * 32 + rd_row) * LD2 + 16 * ks + rd_col);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], dp[qb], 0, 0, 0);
+                }
+            }
+
+            // ---- fused elementwise: scale, bias, mask, sigmoid (and its derivative), in registers
+            const int srow0 = t * BN + nb * 32 + 4 * g;     // streamed row of register i: srow0 + 8 (i/4) + i%4
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float tt = __builtin_fmaf(s[qb][i], c1, c0);
+                    // backward only: keep 2^t finite so that (1 - P) = 2^t P below is never inf * 0
+                    if (HAS2) tt = __builtin_fminf(tt, 126.0f);
+                    const float e = __builtin_amdgcn_exp2f(tt);
+                    float pr = __builtin_amdgcn_rcpf(1.0f + e);
+                    if (partial) {
+                        const int r = srow0 + 8 * (i >> 2) + (i & 3);
+                        pr = (r < n) ? pr : 0.f;
+                    }
+                    s[qb][i] = pr;
+                    // dS = P (1 - P) dP with 1 - P = 2^t P: exact on the saturated tail where 1 - P
+                    // would cancel in fp32
+                    if (HAS2) dp[qb][i] = pr * (e * pr) * dp[qb][i];
+                }
+            }
+
+            // ---- contractions over the 32 streamed rows of this block (two MFMA steps of 16)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                bf16x8 pb[QB], dsb[HAS2 ? QB : 1];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    pb[qb] = acc_to_operand(s[qb], half);
+                    if (HAS2) dsb[qb] = acc_to_operand(dp[qb], half);
+                }
+                const int r_lo = nb * 32 + 16 * half + tr_row;
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) {
+                    if (MODE == FWD) {          // O^T += V^T P^T
+                        const bf16_t *a = t2 + r_lo * LD2 + 32 * mb + tr_col;
+                        const bf16x8 vt = lds_read_tr(a, a + 8 * LD2);
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb)
+                            acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb], acc0[qb][mb], 0, 0, 0);
+                    } else {                    // dQ^T += K^T dS^T   |   dK^T += Q^T dS
+                        const bf16_t *a = t1 + r_lo * LD1 + 32 * mb + tr_col;
+                        const bf16x8 yt = lds_read_tr(a, a + 8 * LD1);
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb)
+                            acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb], acc0[qb][mb], 0, 0, 0);
+                        if (MODE == DKDV) {     // dV^T += dO^T P
+                            const bf16_t *a2 = t2 + r_lo * LD2 + 32 * mb + tr_col;
+                            const bf16x8 gt = lds_read_tr(a2, a2 + 8 * LD2);
+#pragma unroll
+                            for (int qb = 0; qb < QB; ++qb)
+                                acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb], acc1[qb][mb], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+
+        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
+    // register i holds head-dim column 32 mb + 8 (i/4) + 4 g + (i%4): four consecutive columns per store.
+    const float oscale = (MODE == FWD) ? 1.0f : p.scale;            // dQ and dK carry the factor `scale`
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int r = wrow0 + 32 * qb + c;
+        if (r >= p.N) continue;
+        const bool ok = r < n;                                       // padded owner rows are written as zero
+        const size_t off = slice + (size_t)r * row_stride + 4 * g;
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                u32x2 w0 = {0u, 0u};
+                if (ok) {
+                    w0[0] = pack_bf16(acc0[qb][mb][4 * q4 + 0] * oscale, acc0[qb][mb][4 * q4 + 1] * oscale);
+                    w0[1] = pack_bf16(acc0[qb][mb][4 * q4 + 2] * oscale, acc0[qb][mb][4 * q4 + 3] * oscale);
+                }
+                *reinterpret_cast<u32x2 *>(p.out0 + off + 32 * mb + 8 * q4) = w0;
+                if (MODE == DKDV) {
+                    u32x2 w1 = {0u, 0u};
+                    if (ok) {
+                        w1[0] = pack_bf16(acc1[qb][mb][4 * q4 + 0], acc1[qb][mb][4 * q4 + 1]);
+                        w1[1] = pack_bf16(acc1[qb][mb][4 * q4 + 2], acc1[qb][mb][4 * q4 + 3]);
+                    }
+                    *reinterpret_cast<u32x2 *>(p.out1 + off + 32 * mb + 8 * q4) = w1;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace sigattn

@@ -1,0 +1,82 @@
+"""The C-ABI library: it loads without a GPU, exports every symbol the header declares, and rejects
+bad arguments on the host (before any HIP call), so all of this runs on the CPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_27124_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "sigmoid_attn.h")).read()
+    declared = set(re.findall(r"\b(sigmoid_attn_\w+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(lib):
+    assert B.sigmoid_attn_version() >= 100
+    assert B.sigmoid_attn_strerror(0) == "success"
+    texts = {B.sigmoid_attn_strerror(c) for c in range(-6, 1)}
+    assert len(texts) == 7 and "unknown" in B.sigmoid_attn_strerror(-99)
+
+
+def test_fwd_argument_validation(lib):
+    p = 4096  # a fake, 16-byte aligned, never dereferenced device address
+    ok = dict(B=2, N=256, H=2, d=64)
+
+    def fwd(q=p, k=p, v=p, o=p, sl=p, b=p, scale=0.125, **kw):
+        s = dict(ok); s.update(kw)
+        return lib.sigmoid_attn_fwd(q, k, v, o, sl, b, scale, s["B"], s["N"], s["H"], s["d"], None)
+
+    assert fwd(q=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(o=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(sl=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(b=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(B=0) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(N=-1) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(H=0) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(scale=float("nan")) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(scale=float("inf")) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(d=96) == B.SIGATTN_ERR_UNSUPPORTED_D
+    assert fwd(d=32) == B.SIGATTN_ERR_UNSUPPORTED_D
+    assert fwd(k=p + 8) == B.SIGATTN_ERR_MISALIGNED
+    assert fwd(o=p + 2) == B.SIGATTN_ERR_MISALIGNED
+    assert fwd(B=70000, H=1) == B.SIGATTN_ERR_TOO_LARGE
+
+
+def test_bwd_argument_validation(lib):
+    p = 4096
+
+    def bwd(q=p, k=p, v=p, g=p, dq=p, dk=p, dv=p, sl=p, b=p, scale=0.125, Bn=2, N=256, H=2, d=64, ws=None, wsb=0):
+        return lib.sigmoid_attn_bwd(q, k, v, g, dq, dk, dv, sl, b, scale, Bn, N, H, d, ws, wsb, None)
+
+    assert bwd(g=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(dv=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(Bn=-3) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(d=80) == B.SIGATTN_ERR_UNSUPPORTED_D
+    assert bwd(dq=p + 4) == B.SIGATTN_ERR_MISALIGNED
+    assert bwd(g=p + 1) == B.SIGATTN_ERR_MISALIGNED
+    need = B.sigmoid_attn_bwd_workspace_bytes(2, 256, 2, 64)
+    if need > 0:
+        assert bwd(ws=None, wsb=0) == B.SIGATTN_ERR_WORKSPACE
+        assert bwd(ws=p, wsb=need - 1) == B.SIGATTN_ERR_WORKSPACE
+    assert B.sigmoid_attn_bwd_workspace_bytes(0, 256, 2, 64) == 0
+    assert B.sigmoid_attn_bwd_workspace_bytes(2, 256, 2, 96) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 8, 1, 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        B.sigmoid_attn_fwd(x, x, x, torch.zeros(1, dtype=torch.int32), torch.zeros(1), 0.125)
