@@ -116,7 +116,7 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
         Params pq = p;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
-        const int e = (d == 64) ? launch<DQ, 64, 2, 4, 64, 80, 72, 2>(pq, s)
+        const int e = (d == 64) ? launch<DQ, 64, 1, 4, 64, 80, 72, 2>(pq, s)
                                 : launch<DQ, 128, 1, 4, 64, 144, 136, 2>(pq, s);
         if (e) return e;
     }

@@ -87,9 +87,10 @@ struct Cfg {
     static constexpr int NB = BN / 32;             // 32-row blocks of a streamed tile
     static constexpr int CH = D / 8;               // 16-byte chunks per row
     static constexpr int PER = (BN * CH) / THREADS;  // chunks per thread per streamed tensor
-    static constexpr size_t LDS_BYTES = 2u * BN * (LD1 + LD2) * sizeof(bf16_t);
+    static constexpr int NBUF = 3;                 // LDS ring: tile t lives in slot t % 3
+    static constexpr size_t LDS_BYTES = (size_t)NBUF * BN * (LD1 + LD2) * sizeof(bf16_t);
     static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
-    static_assert(D % 32 == 0 && BN % 32 == 0, "tile shape");
+    static_assert(D % 32 == 0 && BN % 64 == 0, "tile shape (an even number of 32-row blocks per tile)");
     static_assert(LD1 % 8 == 0 && LD2 % 8 == 0 && LD1 >= D && LD2 >= D, "LDS row stride");
 };
 
@@ -105,15 +106,44 @@ __device__ __forceinline__ void zero_rows(bf16_t *out, size_t slice_base, size_t
     }
 }
 
+// bf16 x 8 times a float, rounded back to bf16 (used once per kernel, on the owner rows).
+__device__ __forceinline__ bf16x8 scale_bf16x8(const bf16x8 v, const float f) {
+    u32x4 r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = pack_bf16((float)v[2 * j] * f, (float)v[2 * j + 1] * f);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// The fused elementwise step on one 32 x 32 score block held in MFMA accumulator layout.
+//   in : s  = t = -(log2 e)(scale * <q, k> + bias)   (scale and bias are already inside the contraction)
+//        dp = dP (backward only)
+//   out: s  = P = sigma(x) = 1 / (1 + 2^t);  dp = dS = P (1 - P) dP, computed as P dP - P (P dP)
+// Streamed rows >= n (register i <-> row srow0 + 8 (i / 4) + i % 4) get P = 0 when MASKED.
+template <bool HAS2, bool MASKED>
+__device__ __forceinline__ void sigmoid_block(f32x16 &s, f32x16 &dp, const int srow0, const int n) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const float e = __builtin_amdgcn_exp2f(s[i]);
+        float pr = __builtin_amdgcn_rcpf(1.0f + e);
+        if (MASKED) pr = (srow0 + 8 * (i >> 2) + (i & 3) < n) ? pr : 0.f;
+        s[i] = pr;
+        if (HAS2) {
+            const float t1 = pr * dp[i];
+            dp[i] = __builtin_fmaf(-pr, t1, t1);
+        }
+    }
+}
+
 template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
 __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
     constexpr bool HAS2 = (MODE != FWD);             // a second owner tensor and a second score tile (dP)
+    constexpr int Q2 = HAS2 ? QB : 1;
     constexpr float LOG2E = 1.4426950408889634f;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t *y1s = reinterpret_cast<bf16_t *>(smem);                 // [2][BN][LD1]
-    bf16_t *y2s = y1s + 2 * BN * LD1;                               // [2][BN][LD2]
+    bf16_t *y1s = reinterpret_cast<bf16_t *>(smem);                 // [NBUF][BN][LD1]
+    bf16_t *y2s = y1s + C::NBUF * BN * LD1;                         // [NBUF][BN][LD2]
 
     const int zh = blockIdx.y;
     const int z = zh / p.H, h = zh - z * p.H;
@@ -140,9 +170,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     const int c = lane & 31, g = lane >> 5;
     const int wrow0 = m0 + wave * 32 * QB;                          // first owner row of this wave
 
+    // sigma(x) = 1 / (1 + 2^t) with t = c1 <q, k> + c0, c1 = -scale log2 e, c0 = -bias log2 e.
+    // c1 is folded into the owner operand of the score contraction (one extra bf16 rounding of that
+    // operand), c0 is the initial value of the score accumulator: t leaves the MFMA ready for exp2.
+    const float c1 = -p.scale * LOG2E;
+    const float c0 = -p.bias[z] * LOG2E;
+    f32x16 cinit;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) cinit[i] = c0;
+
     // ---- owner rows -> registers (B operands): lane holds row c of each 32-block, d = 16 ks + 8 g + 0..7
     bf16x8 xa[QB][C::KS];
-    bf16x8 xb[HAS2 ? QB : 1][HAS2 ? C::KS : 1];
+    bf16x8 xb[Q2][HAS2 ? C::KS : 1];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const int r = wrow0 + 32 * qb + c;
@@ -152,7 +191,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         for (int ks = 0; ks < C::KS; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (ok) t = *reinterpret_cast<const u32x4 *>(x1 + off + 16 * ks);
-            xa[qb][ks] = __builtin_bit_cast(bf16x8, t);
+            xa[qb][ks] = scale_bf16x8(__builtin_bit_cast(bf16x8, t), c1);
             if (HAS2) {
                 u32x4 t2 = {0u, 0u, 0u, 0u};
                 if (ok) t2 = *reinterpret_cast<const u32x4 *>(x2 + off + 16 * ks);
@@ -160,10 +199,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             }
         }
     }
-
-    // sigma(x) = 1 / (1 + 2^t),  t = -(scale * log2 e) * s - bias * log2 e
-    const float c1 = -p.scale * LOG2E;
-    const float c0 = -p.bias[z] * LOG2E;
 
     f32x16 acc0[QB][C::MB];                        // FWD: O^T;  DQ: dQ^T;  DKDV: dK^T
     f32x16 acc1[MODE == DKDV ? QB : 1][MODE == DKDV ? C::MB : 1];   // DKDV: dV^T
@@ -179,7 +214,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             }
         }
 
-    // ---- streamed tile movement: HBM -> registers -> LDS
+    // ---- streamed tile movement: HBM -> registers -> LDS ring slot
     const int ntiles = (n + BN - 1) / BN;
     u32x4 st1[C::PER], st2[C::PER];
     auto load_tile = [&](int t) {
@@ -198,123 +233,137 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             st2[it] = b;
         }
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](int slot) {
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
             const int cid = tid + it * C::THREADS;
             const int r = cid / C::CH;
             const int col = (cid % C::CH) * 8;
-            *reinterpret_cast<u32x4 *>(y1s + (buf * BN + r) * LD1 + col) = st1[it];
-            *reinterpret_cast<u32x4 *>(y2s + (buf * BN + r) * LD2 + col) = st2[it];
+            *reinterpret_cast<u32x4 *>(y1s + (slot * BN + r) * LD1 + col) = st1[it];
+            *reinterpret_cast<u32x4 *>(y2s + (slot * BN + r) * LD2 + col) = st2[it];
         }
     };
 
     // lane-constant pieces of the LDS addresses
-    const int rd_row = c;                          // row-wise A operand: row c, columns 16 ks + 8 g
-    const int rd_col = 8 * g;
+    const int rd_off1 = c * LD1 + 8 * g;           // row-wise A operand: row c, columns 16 ks + 8 g
+    const int rd_off2 = c * LD2 + 8 * g;
     const int i16 = lane & 15, g16 = (lane >> 4) & 1;
     const int tr_row = 4 * g + (i16 >> 2);         // transposed A operand: rows 4 g + 0..3 (and + 8)
     const int tr_col = 16 * g16 + 4 * (i16 & 3);   // 16 output rows (head-dim columns) per 16-lane group
+    const int tr_off1 = tr_row * LD1 + tr_col;
+    const int tr_off2 = tr_row * LD2 + tr_col;
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < ntiles) load_tile(t + 1);
-        const bf16_t *t1 = y1s + buf * BN * LD1;
-        const bf16_t *t2 = y2s + buf * BN * LD2;
-        const bool partial = (t + 1) * BN > n;      // uniform: only the last tile can hold padded rows
-
+    // Stage A of a 32-row block: transposed scores t^T[streamed 32 x owner 32] = Y1 (c1 X1)^T + c0,
+    // and dP^T = Y2 X2^T (backward).
+    auto stage_scores = [&](const bf16_t *t1, const bf16_t *t2, f32x16 (&s)[QB], f32x16 (&dp)[Q2]) {
 #pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-            // ---- transposed scores: S^T[streamed 32 x owner 32] = Y1 X1^T, and dP^T = Y2 X2^T
-            f32x16 s[QB];
-            f32x16 dp[HAS2 ? QB : 1];
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const bf16x8 a1 = lds_read_rows(t1 + rd_off1 + 16 * ks);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[qb][i] = 0.f;
-                if (HAS2) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) dp[qb][i] = 0.f;
-                }
-            }
-#pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks) {
-                const bf16x8 a1 = lds_read_rows(t1 + (nb * 32 + rd_row) * LD1 + 16 * ks + rd_col);
+            for (int qb = 0; qb < QB; ++qb)
+                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], ks == 0 ? cinit : s[qb], 0, 0, 0);
+            if (HAS2) {
+                const bf16x8 a2 = lds_read_rows(t2 + rd_off2 + 16 * ks);
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
-                    s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], s[qb], 0, 0, 0);
-                if (HAS2) {
-                    const bf16x8 a2 = lds_read_rows(t2 + (nb * 32 + rd_row) * LD2 + 16 * ks + rd_col);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], dp[qb], 0, 0, 0);
-                }
+                    dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], ks == 0 ? zero : dp[qb], 0, 0, 0);
             }
+        }
+    };
 
-            // ---- fused elementwise: scale, bias, mask, sigmoid (and its derivative), in registers
-            const int srow0 = t * BN + nb * 32 + 4 * g;     // streamed row of register i: srow0 + 8 (i/4) + i%4
+    // Stage C of a 32-row block: the contractions over its 32 streamed rows (two MFMA steps of 16).
+    auto stage_outputs = [&](const bf16_t *t1, const bf16_t *t2, const f32x16 (&s)[QB], const f32x16 (&dp)[Q2]) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            bf16x8 pb[QB], dsb[Q2];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float tt = __builtin_fmaf(s[qb][i], c1, c0);
-                    // backward only: keep 2^t finite so that (1 - P) = 2^t P below is never inf * 0
-                    if (HAS2) tt = __builtin_fminf(tt, 126.0f);
-                    const float e = __builtin_amdgcn_exp2f(tt);
-                    float pr = __builtin_amdgcn_rcpf(1.0f + e);
-                    if (partial) {
-                        const int r = srow0 + 8 * (i >> 2) + (i & 3);
-                        pr = (r < n) ? pr : 0.f;
-                    }
-                    s[qb][i] = pr;
-                    // dS = P (1 - P) dP with 1 - P = 2^t P: exact on the saturated tail where 1 - P
-                    // would cancel in fp32
-                    if (HAS2) dp[qb][i] = pr * (e * pr) * dp[qb][i];
-                }
+                pb[qb] = acc_to_operand(s[qb], half);
+                if (HAS2) dsb[qb] = acc_to_operand(dp[qb], half);
             }
-
-            // ---- contractions over the 32 streamed rows of this block (two MFMA steps of 16)
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                bf16x8 pb[QB], dsb[HAS2 ? QB : 1];
+            for (int mb = 0; mb < C::MB; ++mb) {
+                if (MODE == FWD) {          // O^T += V^T P^T
+                    const bf16_t *a = t2 + 16 * half * LD2 + tr_off2 + 32 * mb;
+                    const bf16x8 vt = lds_read_tr(a, a + 8 * LD2);
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    pb[qb] = acc_to_operand(s[qb], half);
-                    if (HAS2) dsb[qb] = acc_to_operand(dp[qb], half);
-                }
-                const int r_lo = nb * 32 + 16 * half + tr_row;
+                    for (int qb = 0; qb < QB; ++qb)
+                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb], acc0[qb][mb], 0, 0, 0);
+                } else {                    // dQ^T += K^T dS^T   |   dK^T += Q^T dS
+                    const bf16_t *a = t1 + 16 * half * LD1 + tr_off1 + 32 * mb;
+                    const bf16x8 yt = lds_read_tr(a, a + 8 * LD1);
 #pragma unroll
-                for (int mb = 0; mb < C::MB; ++mb) {
-                    if (MODE == FWD) {          // O^T += V^T P^T
-                        const bf16_t *a = t2 + r_lo * LD2 + 32 * mb + tr_col;
-                        const bf16x8 vt = lds_read_tr(a, a + 8 * LD2);
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb)
-                            acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb], acc0[qb][mb], 0, 0, 0);
-                    } else {                    // dQ^T += K^T dS^T   |   dK^T += Q^T dS
-                        const bf16_t *a = t1 + r_lo * LD1 + 32 * mb + tr_col;
-                        const bf16x8 yt = lds_read_tr(a, a + 8 * LD1);
+                    for (int qb = 0; qb < QB; ++qb)
+                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb], acc0[qb][mb], 0, 0, 0);
+                    if (MODE == DKDV) {     // dV^T += dO^T P
+                        const bf16_t *a2 = t2 + 16 * half * LD2 + tr_off2 + 32 * mb;
+                        const bf16x8 gt = lds_read_tr(a2, a2 + 8 * LD2);
 #pragma unroll
                         for (int qb = 0; qb < QB; ++qb)
-                            acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb], acc0[qb][mb], 0, 0, 0);
-                        if (MODE == DKDV) {     // dV^T += dO^T P
-                            const bf16_t *a2 = t2 + r_lo * LD2 + 32 * mb + tr_col;
-                            const bf16x8 gt = lds_read_tr(a2, a2 + 8 * LD2);
-#pragma unroll
-                            for (int qb = 0; qb < QB; ++qb)
-                                acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb], acc1[qb][mb], 0, 0, 0);
-                        }
+                            acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb], acc1[qb][mb], 0, 0, 0);
                     }
                 }
             }
         }
+    };
 
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
+    // ---- prologue: tiles 0 and 1 into the ring, tile 2 into registers, scores of block 0 in flight
+    load_tile(0);
+    store_tile(0);
+    if (ntiles > 1) {
+        load_tile(1);
+        store_tile(1);
+    }
+    __syncthreads();
+    if (ntiles > 2) load_tile(2);
+
+    f32x16 sbuf[2][QB], dbuf[2][Q2];
+    stage_scores(y1s, y2s, sbuf[0], dbuf[0]);
+
+    // ---- main loop, software-pipelined over 32-row blocks: while the VALU works on block b, the MFMA
+    // pipe holds the scores of block b + 1 (issued first) and the output contractions of block b - 1.
+    int slot = 0;                                   // t % 3
+    for (int t = 0; t < ntiles; ++t) {
+        const int slot_next = (slot == C::NBUF - 1) ? 0 : slot + 1;
+        const bf16_t *t1 = y1s + slot * BN * LD1;
+        const bf16_t *t2 = y2s + slot * BN * LD2;
+        const bool partial = (t + 1) * BN > n;      // uniform: only the last tile can hold padded rows
+        const bool last = (t + 1 == ntiles);
+
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) {
+            const int cur = nb & 1;
+            // scores of the next block (possibly the first block of the next tile)
+            if (nb + 1 < C::NB) {
+                stage_scores(t1 + (nb + 1) * 32 * LD1, t2 + (nb + 1) * 32 * LD2, sbuf[cur ^ 1], dbuf[cur ^ 1]);
+            } else if (!last) {
+                stage_scores(y1s + slot_next * BN * LD1, y2s + slot_next * BN * LD2, sbuf[cur ^ 1], dbuf[cur ^ 1]);
+            }
+            // fused elementwise on this block
+            const int srow0 = t * BN + nb * 32 + 4 * g;
+            if (partial) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    sigmoid_block<HAS2, true>(sbuf[cur][qb], dbuf[cur][HAS2 ? qb : 0], srow0, n);
+            } else {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    sigmoid_block<HAS2, false>(sbuf[cur][qb], dbuf[cur][HAS2 ? qb : 0], srow0, n);
+            }
+            // contractions over this block's streamed rows
+            stage_outputs(t1 + nb * 32 * LD1, t2 + nb * 32 * LD2, sbuf[cur], dbuf[cur]);
+        }
+
+        // tile t + 2 -> the slot tile t - 1 used (every wave left it before the previous barrier);
+        // it becomes visible at this barrier, one full tile before its first read.
+        if (t + 2 < ntiles) {
+            const int slot_n2 = (slot_next == C::NBUF - 1) ? 0 : slot_next + 1;
+            store_tile(slot_n2);
+        }
         __syncthreads();
+        if (t + 3 < ntiles) load_tile(t + 3);
+        slot = slot_next;
     }
 
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
