@@ -9,10 +9,6 @@ using namespace sigattn;
 
 namespace {
 
-struct Shape {
-    int B, N, H, d;
-};
-
 int check_shape(int B, int N, int H, int d) {
     if (B <= 0 || N <= 0 || H <= 0) return SIGATTN_ERR_INVALID_ARG;
     if (d != 64 && d != 128) return SIGATTN_ERR_UNSUPPORTED_D;
@@ -31,6 +27,11 @@ int launch(const Params &p, hipStream_t stream) {
     dim3 grid((unsigned)tiles, (unsigned)(p.B * p.H), 1);
     dim3 block(C::THREADS, 1, 1);
     auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC>;
+    if (C::LDS_BYTES > 65536) {   // more dynamic LDS than the default limit: opt in (idempotent, host-side only)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)C::LDS_BYTES) != hipSuccess)
+            return SIGATTN_ERR_LAUNCH;
+    }
     hipLaunchKernelGGL(kern, grid, block, C::LDS_BYTES, stream, p);
     return hipGetLastError() == hipSuccess ? SIGATTN_OK : SIGATTN_ERR_LAUNCH;
 }
@@ -78,8 +79,8 @@ int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
     p.scale = scale;
     p.B = B; p.N = N_max; p.H = H;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (d == 64) return launch<FWD, 64, 2, 4, 64, 72, 80, 2>(p, s);
-    return launch<FWD, 128, 1, 4, 64, 136, 144, 2>(p, s);
+    if (d == 64) return launch<FWD, 64, 2, 8, 64, 72, 80, 1>(p, s);
+    return launch<FWD, 128, 1, 8, 64, 136, 144, 1>(p, s);
 }
 
 static int bwd_common(const void *q, const void *k, const void *v, const void *d_o,
@@ -109,15 +110,15 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
         pk.out0 = static_cast<bf16_t *>(dk);
         pk.out1 = static_cast<bf16_t *>(dv);
         const int e = (d == 64) ? launch<DKDV, 64, 1, 4, 64, 80, 80, 2>(pk, s)
-                                : launch<DKDV, 128, 1, 4, 64, 144, 144, 1>(pk, s);
+                                : launch<DKDV, 128, 1, 8, 64, 144, 144, 1>(pk, s);
         if (e) return e;
     }
     if (want_dq) {           // Alg. 2: dQ (owner = query tile)
         Params pq = p;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
-        const int e = (d == 64) ? launch<DQ, 64, 1, 4, 64, 80, 72, 2>(pq, s)
-                                : launch<DQ, 128, 1, 4, 64, 144, 136, 2>(pq, s);
+        const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 80, 72, 1>(pq, s)
+                                : launch<DQ, 128, 1, 8, 64, 144, 136, 1>(pq, s);
         if (e) return e;
     }
     return SIGATTN_OK;

@@ -38,6 +38,11 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 enum Mode { FWD = 0, DQ = 1, DKDV = 2 };
 
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+
 struct Params {
     const bf16_t *q, *k, *v, *d_o;   // inputs  [B, N, H, D]
     bf16_t *out0;                    // FWD: O;  DQ: dQ;  DKDV: dK
@@ -87,7 +92,7 @@ struct Cfg {
     static constexpr int NB = BN / 32;             // 32-row blocks of a streamed tile
     static constexpr int CH = D / 8;               // 16-byte chunks per row
     static constexpr int PER = (BN * CH) / THREADS;  // chunks per thread per streamed tensor
-    static constexpr int NBUF = 3;                 // LDS ring: tile t lives in slot t % 3
+    static constexpr int NBUF = 4;                 // LDS ring: tile t lives in slot t % 4
     static constexpr size_t LDS_BYTES = (size_t)NBUF * BN * (LD1 + LD2) * sizeof(bf16_t);
     static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
     static_assert(D % 32 == 0 && BN % 64 == 0, "tile shape (an even number of 32-row blocks per tile)");
@@ -217,20 +222,19 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     // ---- streamed tile movement: HBM -> registers -> LDS ring slot
     const int ntiles = (n + BN - 1) / BN;
     u32x4 st1[C::PER], st2[C::PER];
-    auto load_tile = [&](int t) {
+    auto load_tile = [&](int t) {   // branch-free: rows beyond the valid length read a clamped row, then become 0
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
             const int cid = tid + it * C::THREADS;
             const int r = t * BN + cid / C::CH;
             const int col = (cid % C::CH) * 8;
-            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (r < n) {    // rows beyond the valid length are filled with zeros, never read
-                const size_t off = slice + (size_t)r * row_stride + col;
-                a = *reinterpret_cast<const u32x4 *>(y1 + off);
-                b = *reinterpret_cast<const u32x4 *>(y2 + off);
-            }
-            st1[it] = a;
-            st2[it] = b;
+            const bool ok = r < n;
+            const size_t off = slice + (size_t)(ok ? r : n - 1) * row_stride + col;
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(y1 + off);
+            const u32x4 b = *reinterpret_cast<const u32x4 *>(y2 + off);
+            const u32x4 z4 = {0u, 0u, 0u, 0u};
+            st1[it] = ok ? a : z4;
+            st2[it] = ok ? b : z4;
         }
     };
     auto store_tile = [&](int slot) {
@@ -272,16 +276,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         }
     };
 
-    // Stage C of a 32-row block: the contractions over its 32 streamed rows (two MFMA steps of 16).
-    auto stage_outputs = [&](const bf16_t *t1, const bf16_t *t2, const f32x16 (&s)[QB], const f32x16 (&dp)[Q2]) {
+    // Stage C of a 32-row block: the contractions over its 32 streamed rows (two MFMA steps of 16), from
+    // the bf16 operands stage B left behind.
+    auto stage_outputs = [&](const bf16_t *t1, const bf16_t *t2, const bf16x8 (&pb)[QB][2], const bf16x8 (&dsb)[Q2][2]) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            bf16x8 pb[QB], dsb[Q2];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                pb[qb] = acc_to_operand(s[qb], half);
-                if (HAS2) dsb[qb] = acc_to_operand(dp[qb], half);
-            }
 #pragma unroll
             for (int mb = 0; mb < C::MB; ++mb) {
                 if (MODE == FWD) {          // O^T += V^T P^T
@@ -289,26 +288,53 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                     const bf16x8 vt = lds_read_tr(a, a + 8 * LD2);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
-                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb], acc0[qb][mb], 0, 0, 0);
+                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb][half], acc0[qb][mb], 0, 0, 0);
                 } else {                    // dQ^T += K^T dS^T   |   dK^T += Q^T dS
                     const bf16_t *a = t1 + 16 * half * LD1 + tr_off1 + 32 * mb;
                     const bf16x8 yt = lds_read_tr(a, a + 8 * LD1);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
-                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb], acc0[qb][mb], 0, 0, 0);
+                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb][half], acc0[qb][mb], 0, 0, 0);
                     if (MODE == DKDV) {     // dV^T += dO^T P
                         const bf16_t *a2 = t2 + 16 * half * LD2 + tr_off2 + 32 * mb;
                         const bf16x8 gt = lds_read_tr(a2, a2 + 8 * LD2);
 #pragma unroll
                         for (int qb = 0; qb < QB; ++qb)
-                            acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb], acc1[qb][mb], 0, 0, 0);
+                            acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb][half], acc1[qb][mb], 0, 0, 0);
                     }
                 }
             }
         }
     };
 
-    // ---- prologue: tiles 0 and 1 into the ring, tile 2 into registers, scores of block 0 in flight
+    // Score accumulators and bf16 operands, double buffered by block parity.
+    f32x16 sbuf[2][QB], dbuf[2][Q2];
+    bf16x8 pbuf[2][QB][2], dsbuf[2][Q2][2];
+
+    // One pipeline step for the block of parity PAR.  Three independent pieces of work sit in one basic
+    // block: the score MFMAs of the NEXT block, the output MFMAs of the PREVIOUS block, and the sigmoid of
+    // THIS block on the VALU, so that the matrix pipe and the VALU can run side by side within one wave.
+    auto step = [&](auto masked_c, auto has_next_c, auto par_c, const bf16_t *n1, const bf16_t *n2,
+                    const bf16_t *p1, const bf16_t *p2, const int srow0) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr bool HAS_NEXT = decltype(has_next_c)::value;
+        constexpr int PAR = decltype(par_c)::value;
+        if (HAS_NEXT) stage_scores(n1, n2, sbuf[PAR ^ 1], dbuf[PAR ^ 1]);
+        stage_outputs(p1, p2, pbuf[PAR ^ 1], dsbuf[PAR ^ 1]);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            sigmoid_block<HAS2, MASKED>(sbuf[PAR][qb], dbuf[PAR][HAS2 ? qb : 0], srow0, n);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                pbuf[PAR][qb][half] = acc_to_operand(sbuf[PAR][qb], half);
+                if (HAS2) dsbuf[PAR][qb][half] = acc_to_operand(dbuf[PAR][qb], half);
+            }
+        }
+    };
+    using std_true = IntC<1>;
+    using std_false = IntC<0>;
+
+    // ---- prologue: tiles 0 and 1 into the ring, tile 2 into registers, scores of block 0 computed
     load_tile(0);
     store_tile(0);
     if (ntiles > 1) {
@@ -316,54 +342,68 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         store_tile(1);
     }
     __syncthreads();
-    if (ntiles > 2) load_tile(2);
+    load_tile(2);
 
-    f32x16 sbuf[2][QB], dbuf[2][Q2];
     stage_scores(y1s, y2s, sbuf[0], dbuf[0]);
+    {   // the "previous block" of block 0 contributes nothing: zero operands
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                pbuf[1][qb][half] = __builtin_bit_cast(bf16x8, z4);
+                if (HAS2) dsbuf[1][qb][half] = __builtin_bit_cast(bf16x8, z4);
+            }
+    }
 
-    // ---- main loop, software-pipelined over 32-row blocks: while the VALU works on block b, the MFMA
-    // pipe holds the scores of block b + 1 (issued first) and the output contractions of block b - 1.
-    int slot = 0;                                   // t % 3
-    for (int t = 0; t < ntiles; ++t) {
-        const int slot_next = (slot == C::NBUF - 1) ? 0 : slot + 1;
+    // ---- main loop over all tiles but the last: no padded rows, every block has a successor
+    int slot = 0;                                    // t % NBUF
+    const bf16_t *prev1 = y1s, *prev2 = y2s;         // block whose output contractions are still due
+    for (int t = 0; t + 1 < ntiles; ++t) {
+        const int slot_next = (slot + 1) & (C::NBUF - 1);
         const bf16_t *t1 = y1s + slot * BN * LD1;
         const bf16_t *t2 = y2s + slot * BN * LD2;
-        const bool partial = (t + 1) * BN > n;      // uniform: only the last tile can hold padded rows
-        const bool last = (t + 1 == ntiles);
-
 #pragma unroll
         for (int nb = 0; nb < C::NB; ++nb) {
-            const int cur = nb & 1;
-            // scores of the next block (possibly the first block of the next tile)
-            if (nb + 1 < C::NB) {
-                stage_scores(t1 + (nb + 1) * 32 * LD1, t2 + (nb + 1) * 32 * LD2, sbuf[cur ^ 1], dbuf[cur ^ 1]);
-            } else if (!last) {
-                stage_scores(y1s + slot_next * BN * LD1, y2s + slot_next * BN * LD2, sbuf[cur ^ 1], dbuf[cur ^ 1]);
-            }
-            // fused elementwise on this block
+            const bf16_t *n1 = (nb + 1 < C::NB) ? t1 + (nb + 1) * 32 * LD1 : y1s + slot_next * BN * LD1;
+            const bf16_t *n2 = (nb + 1 < C::NB) ? t2 + (nb + 1) * 32 * LD2 : y2s + slot_next * BN * LD2;
             const int srow0 = t * BN + nb * 32 + 4 * g;
-            if (partial) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    sigmoid_block<HAS2, true>(sbuf[cur][qb], dbuf[cur][HAS2 ? qb : 0], srow0, n);
-            } else {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    sigmoid_block<HAS2, false>(sbuf[cur][qb], dbuf[cur][HAS2 ? qb : 0], srow0, n);
-            }
-            // contractions over this block's streamed rows
-            stage_outputs(t1 + nb * 32 * LD1, t2 + nb * 32 * LD2, sbuf[cur], dbuf[cur]);
+            if (nb & 1) step(std_false{}, std_true{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
+            else        step(std_false{}, std_true{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
+            prev1 = t1 + nb * 32 * LD1;
+            prev2 = t2 + nb * 32 * LD2;
         }
-
-        // tile t + 2 -> the slot tile t - 1 used (every wave left it before the previous barrier);
-        // it becomes visible at this barrier, one full tile before its first read.
-        if (t + 2 < ntiles) {
-            const int slot_n2 = (slot_next == C::NBUF - 1) ? 0 : slot_next + 1;
-            store_tile(slot_n2);
-        }
+        // tile t + 2 goes to slot (t + 2) % 4 = (t - 2) % 4, last read during tile t - 1 (as the previous
+        // block of its first step); every wave passed the barrier that ended tile t - 1.  It becomes
+        // visible at this barrier, a full tile before its first read at the end of tile t + 1.
+        // (Past the end these are harmless: the registers then hold zeros and the slot is not live.)
+        store_tile((slot + 2) & (C::NBUF - 1));
         __syncthreads();
-        if (t + 3 < ntiles) load_tile(t + 3);
+        load_tile(t + 3);
         slot = slot_next;
+    }
+
+    // ---- last tile: rows >= n masked, the final block has no successor
+    {
+        const int t = ntiles - 1;
+        const bf16_t *t1 = y1s + slot * BN * LD1;
+        const bf16_t *t2 = y2s + slot * BN * LD2;
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) {
+            const bf16_t *n1 = t1 + (nb + 1) * 32 * LD1;
+            const bf16_t *n2 = t2 + (nb + 1) * 32 * LD2;
+            const int srow0 = t * BN + nb * 32 + 4 * g;
+            if (nb + 1 < C::NB) {
+                if (nb & 1) step(std_true{}, std_true{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
+                else        step(std_true{}, std_true{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
+            } else {
+                if (nb & 1) step(std_true{}, std_false{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
+                else        step(std_true{}, std_false{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
+            }
+            prev1 = t1 + nb * 32 * LD1;
+            prev2 = t2 + nb * 32 * LD2;
+        }
+        stage_outputs(prev1, prev2, pbuf[(C::NB - 1) & 1], dsbuf[(C::NB - 1) & 1]);
     }
 
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
