@@ -12,7 +12,7 @@ namespace {
 int check_shape(int B, int N, int H, int d) {
     if (B <= 0 || N <= 0 || H <= 0) return SIGATTN_ERR_INVALID_ARG;
     if (d != 64 && d != 128) return SIGATTN_ERR_UNSUPPORTED_D;
-    if ((long long)B * H > 65535LL) return SIGATTN_ERR_TOO_LARGE;          // grid.y limit
+    if ((long long)B * H > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;     // grid.x limit
     if ((long long)B * N * H * d >= (1LL << 40)) return SIGATTN_ERR_TOO_LARGE;
     return SIGATTN_OK;
 }
@@ -23,8 +23,9 @@ template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
 int launch(const Params &p, hipStream_t stream) {
     using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
     const long long tiles = ((long long)p.N + C::BM - 1) / C::BM;
-    if (tiles > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;
-    dim3 grid((unsigned)tiles, (unsigned)(p.B * p.H), 1);
+    const long long wgs = tiles * p.B * p.H;                                // one workgroup per owner tile
+    if (wgs > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;
+    dim3 grid((unsigned)wgs, 1, 1);
     dim3 block(C::THREADS, 1, 1);
     auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC>;
     if (C::LDS_BYTES > 65536) {   // more dynamic LDS than the default limit: opt in (idempotent, host-side only)

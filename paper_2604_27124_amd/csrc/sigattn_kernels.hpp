@@ -120,21 +120,87 @@ __device__ __forceinline__ bf16x8 scale_bf16x8(const bf16x8 v, const float f) {
 }
 
 // The fused elementwise step on one 32 x 32 score block held in MFMA accumulator layout.
-//   in : s  = t = -(log2 e)(scale * <q, k> + bias)   (scale and bias are already inside the contraction)
-//        dp = dP (backward only)
-//   out: s  = P = sigma(x) = 1 / (1 + 2^t);  dp = dS = P (1 - P) dP, computed as P dP - P (P dP)
+//   in : s  = t' = -(log2 e) scale <q, k>   (the factor is already inside the contraction)
+//        dp = dP (backward only);  cb = 2^(-bias log2 e)
+//   out: s  = P = sigma(x) = 1 / (1 + cb 2^t');  dp = dS = P (1 - P) dP, computed as P dP - P (P dP)
+// cb is finite and non-zero, so cb * 2^t' is 0, finite or +inf but never NaN, and P lands in [0, 1].
 // Streamed rows >= n (register i <-> row srow0 + 8 (i / 4) + i % 4) get P = 0 when MASKED.
 template <bool HAS2, bool MASKED>
-__device__ __forceinline__ void sigmoid_block(f32x16 &s, f32x16 &dp, const int srow0, const int n) {
+__device__ __forceinline__ void sigmoid_block(f32x16 &s, f32x16 &dp, const float cb, const int srow0, const int n) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const float e = __builtin_amdgcn_exp2f(s[i]);
-        float pr = __builtin_amdgcn_rcpf(1.0f + e);
+        float pr = __builtin_amdgcn_rcpf(__builtin_fmaf(cb, e, 1.0f));
         if (MASKED) pr = (srow0 + 8 * (i >> 2) + (i & 3) < n) ? pr : 0.f;
         s[i] = pr;
         if (HAS2) {
             const float t1 = pr * dp[i];
             dp[i] = __builtin_fmaf(-pr, t1, t1);
+        }
+    }
+}
+
+// Longest-first work mapping.  The launch is a 1-D grid with one workgroup per owner tile of every
+// (z, h); hardware hands consecutive workgroup ids to the 8 XCDs round-robin and to free CUs in order.
+// Ids are therefore mapped so that the tiles of the LONGEST sequences come first (their cost is
+// proportional to the sequence's valid length) and every XCD receives every 8th tile of that sorted list;
+// wholly padded tiles, which only write zeros, come last.  Sequences are ranked inside the kernel from
+// seqlens (B <= MAP_MAX_B; larger batches keep batch order), so the host never needs the lengths.
+constexpr int MAP_MAX_B = 256;
+
+template <int BM, int THREADS>
+__device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n, int &m0) {
+    __shared__ int s_len[MAP_MAX_B];      // clamped valid length, by batch index
+    __shared__ int s_seq[MAP_MAX_B];      // batch index, by rank (longest first)
+    const int T = (p.N + BM - 1) / BM;    // owner tiles per (z, h), padded ones included
+    const int id = blockIdx.x;
+    const bool sorted = p.B <= MAP_MAX_B;
+    if (sorted) {
+        for (int t = threadIdx.x; t < p.B; t += THREADS) {
+            const int v = p.seqlens[t];
+            s_len[t] = v < 0 ? 0 : (v > p.N ? p.N : v);
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < p.B; t += THREADS) {
+            const int mine = s_len[t];
+            int rank = 0;
+            for (int u = 0; u < p.B; ++u) {
+                const int o = s_len[u];
+                rank += (o > mine || (o == mine && u < t)) ? 1 : 0;
+            }
+            s_seq[rank] = t;
+        }
+        __syncthreads();
+    }
+    auto len_of = [&](int b) {
+        if (sorted) return s_len[b];
+        const int v = p.seqlens[b];
+        return v < 0 ? 0 : (v > p.N ? p.N : v);
+    };
+    // valid tiles, longest sequence first; then the padded tiles
+    int rest = id;
+    bool found = false;
+    z = 0; h = 0; n = 0; m0 = 0;
+    for (int r = 0; r < p.B && !found; ++r) {
+        const int b = sorted ? s_seq[r] : r;
+        const int len = len_of(b);
+        const int cnt = ((len + BM - 1) / BM) * p.H;
+        if (rest < cnt) {
+            z = b; n = len; h = rest % p.H; m0 = (rest / p.H) * BM;
+            found = true;
+        } else {
+            rest -= cnt;
+        }
+    }
+    for (int b = 0; b < p.B && !found; ++b) {
+        const int len = len_of(b);
+        const int first = (len + BM - 1) / BM;
+        const int cnt = (T - first) * p.H;
+        if (rest < cnt) {
+            z = b; n = len; h = rest % p.H; m0 = (first + rest / p.H) * BM;
+            found = true;
+        } else {
+            rest -= cnt;
         }
     }
 }
@@ -150,11 +216,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     bf16_t *y1s = reinterpret_cast<bf16_t *>(smem);                 // [NBUF][BN][LD1]
     bf16_t *y2s = y1s + C::NBUF * BN * LD1;                         // [NBUF][BN][LD2]
 
-    const int zh = blockIdx.y;
-    const int z = zh / p.H, h = zh - z * p.H;
-    int n = p.seqlens[z];
-    n = n < 0 ? 0 : (n > p.N ? p.N : n);
-    const int m0 = blockIdx.x * C::BM;                              // first owner row of this workgroup
+    // Work mapping (1-D grid over every owner tile of every (z, h)): see map_work().
+    int z, h, n, m0;
+    map_work<C::BM, C::THREADS>(p, z, h, n, m0);
+    z = __builtin_amdgcn_readfirstlane(z);      // uniform across the workgroup: keep them in scalar registers
+    h = __builtin_amdgcn_readfirstlane(h);
+    n = __builtin_amdgcn_readfirstlane(n);
+    m0 = __builtin_amdgcn_readfirstlane(m0);
     const int m1 = (m0 + C::BM < p.N) ? m0 + C::BM : p.N;
     const size_t row_stride = (size_t)p.H * D;
     const size_t slice = ((size_t)z * p.N * p.H + h) * D;           // element offset of row 0 of (z, h)
@@ -175,14 +243,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     const int c = lane & 31, g = lane >> 5;
     const int wrow0 = m0 + wave * 32 * QB;                          // first owner row of this wave
 
-    // sigma(x) = 1 / (1 + 2^t) with t = c1 <q, k> + c0, c1 = -scale log2 e, c0 = -bias log2 e.
+    // sigma(x) = 1 / (1 + cb 2^t') with t' = c1 <q, k>, c1 = -scale log2 e, cb = 2^(-bias log2 e).
     // c1 is folded into the owner operand of the score contraction (one extra bf16 rounding of that
-    // operand), c0 is the initial value of the score accumulator: t leaves the MFMA ready for exp2.
+    // operand), so t' leaves the MFMA ready for exp2; cb rides on the FMA that forms the denominator.
+    // The exponent of cb is clamped to +-126 (|bias| <= 87.3 is exact; beyond that sigma is saturated).
     const float c1 = -p.scale * LOG2E;
-    const float c0 = -p.bias[z] * LOG2E;
-    f32x16 cinit;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) cinit[i] = c0;
+    const float cb = __builtin_amdgcn_exp2f(__builtin_fminf(__builtin_fmaxf(-p.bias[z] * LOG2E, -126.0f), 126.0f));
 
     // ---- owner rows -> registers (B operands): lane holds row c of each 32-block, d = 16 ks + 8 g + 0..7
     bf16x8 xa[QB][C::KS];
@@ -257,18 +323,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     const int tr_off1 = tr_row * LD1 + tr_col;
     const int tr_off2 = tr_row * LD2 + tr_col;
 
-    // Stage A of a 32-row block: transposed scores t^T[streamed 32 x owner 32] = Y1 (c1 X1)^T + c0,
+    // Stage A of a 32-row block: transposed scores t'^T[streamed 32 x owner 32] = Y1 (c1 X1)^T,
     // and dP^T = Y2 X2^T (backward).
     auto stage_scores = [&](const bf16_t *t1, const bf16_t *t2, f32x16 (&s)[QB], f32x16 (&dp)[Q2]) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
             const bf16x8 a1 = lds_read_rows(t1 + rd_off1 + 16 * ks);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
-                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], ks == 0 ? cinit : s[qb], 0, 0, 0);
+                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], ks == 0 ? zero : s[qb], 0, 0, 0);
             if (HAS2) {
                 const bf16x8 a2 = lds_read_rows(t2 + rd_off2 + 16 * ks);
-                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
                     dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], ks == 0 ? zero : dp[qb], 0, 0, 0);
@@ -323,7 +389,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         stage_outputs(p1, p2, pbuf[PAR ^ 1], dsbuf[PAR ^ 1]);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            sigmoid_block<HAS2, MASKED>(sbuf[PAR][qb], dbuf[PAR][HAS2 ? qb : 0], srow0, n);
+            sigmoid_block<HAS2, MASKED>(sbuf[PAR][qb], dbuf[PAR][HAS2 ? qb : 0], cb, srow0, n);
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 pbuf[PAR][qb][half] = acc_to_operand(sbuf[PAR][qb], half);

@@ -52,7 +52,7 @@ def test_fwd_argument_validation(lib):
     assert fwd(d=32) == B.SIGATTN_ERR_UNSUPPORTED_D
     assert fwd(k=p + 8) == B.SIGATTN_ERR_MISALIGNED
     assert fwd(o=p + 2) == B.SIGATTN_ERR_MISALIGNED
-    assert fwd(B=70000, H=1) == B.SIGATTN_ERR_TOO_LARGE
+    assert fwd(B=1 << 20, N=1 << 14, H=1) == B.SIGATTN_ERR_TOO_LARGE  # 2^40 elements per tensor
 
 
 def test_bwd_argument_validation(lib):
