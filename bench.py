@@ -18,27 +18,36 @@ import time
 import numpy as np
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense bf16 MFMA
+# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+# profiles/sigattn_kernels_long_d64_N8192_hbm_traffic.md (calibrated against a 1 GiB copy); only valid for
+# the workload and kernel it was measured on.
+MEASURED_TRAFFIC_BYTES = {("long", 0, "bwd_dkdv"): int(505.7 * 2 ** 20)}
 PAPER_CONTEXT = "paper: 515.6 TFLOPS fwd / 373.5 bwd on H100, d=128, N=16384, unpadded (another machine; context only)"
 
 
-def cpu_baseline(w, budget_s: float = 15.0):
-    """The fp64 oracle, as it stands, timed on the host cores over whole (z, h) slices of the shortest
-    sequence of this workload until about budget_s seconds have been spent."""
+def cpu_baseline(w, budget_s: float = 20.0):
+    """The fp64 oracle, as it stands, timed on the host cores over whole (z, h) slices of this workload,
+    shortest sequence first, until about budget_s seconds have been spent (a bounded sample)."""
     import oracle
-    z = int(np.argmin(np.where(w.seqlens > 0, w.seqlens, np.iinfo(np.int32).max)))
-    n = int(w.seqlens[z])
-    per_slice = 14 * w.d * n * n
-    done, t0 = 0, time.perf_counter()
-    for h in range(w.H):
-        oracle.fwd(w.q, w.k, w.v, w.seqlens, w.bias, w.scale, slices=[(z, h)])
-        oracle.bwd(w.q, w.k, w.v, w.d_o, w.seqlens, w.bias, w.scale, slices=[(z, h)])
-        done += 1
+    order = [int(z) for z in np.argsort(w.seqlens, kind="stable") if w.seqlens[z] > 0]
+    done, flops, t0 = [], 0, time.perf_counter()
+    for z in order:
+        n = int(w.seqlens[z])
+        for h in range(w.H):
+            oracle.fwd(w.q, w.k, w.v, w.seqlens, w.bias, w.scale, slices=[(z, h)])
+            oracle.bwd(w.q, w.k, w.v, w.d_o, w.seqlens, w.bias, w.scale, slices=[(z, h)])
+            flops += 14 * w.d * n * n
+            done.append((z, h))
+            if time.perf_counter() - t0 > budget_s:
+                break
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
-    return {"value": done * per_slice / dt / 1e12, "unit": "TFLOPS", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"fwd+bwd of {done} (z,h) slice(s) of sequence z={z} (n={n}, d={w.d}) of workload "
-                      f"'{w.name}', {dt:.1f} s, fp64 plain loops",
+    zs = sorted({z for z, _ in done})
+    return {"value": flops / dt / 1e12, "unit": "TFLOPS", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"fwd+bwd of {len(done)} of {len(order) * w.H} (z,h) slices of workload '{w.name}' "
+                      f"(sequences {zs}, lengths {[int(w.seqlens[z]) for z in zs]}, d={w.d}), shortest first, "
+                      f"{dt:.1f} s, fp64 plain loops",
             "seconds": dt}
 
 
@@ -123,7 +132,7 @@ def main() -> int:
                            "bwd": round(f_bwd / ((mean_ms[1] + mean_ms[2]) * 1e-3) / 1e12, 1)},
         "roofline": {"bound": "mfma", "kernel": names[dom], "achieved": round(achieved, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, w.seed, names[dom]))},
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
