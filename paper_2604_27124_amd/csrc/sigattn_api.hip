@@ -19,15 +19,15 @@ int check_shape(int B, int N, int H, int d) {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING>
 int launch(const Params &p, hipStream_t stream) {
-    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
+    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2, RING>;
     const long long tiles = ((long long)p.N + C::BM - 1) / C::BM;
     const long long wgs = tiles * p.B * p.H;                                // one workgroup per owner tile
     if (wgs > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;
     dim3 grid((unsigned)wgs, 1, 1);
     dim3 block(C::THREADS, 1, 1);
-    auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC>;
+    auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC, RING>;
     if (C::LDS_BYTES > 65536) {   // more dynamic LDS than the default limit: opt in (idempotent, host-side only)
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)C::LDS_BYTES) != hipSuccess)
@@ -80,8 +80,8 @@ int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
     p.scale = scale;
     p.B = B; p.N = N_max; p.H = H;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (d == 64) return launch<FWD, 64, 2, 8, 64, 72, 80, 1>(p, s);
-    return launch<FWD, 128, 1, 8, 64, 136, 144, 1>(p, s);
+    if (d == 64) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
+    return launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(p, s);
 }
 
 static int bwd_common(const void *q, const void *k, const void *v, const void *d_o,
@@ -110,16 +110,16 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
         Params pk = p;
         pk.out0 = static_cast<bf16_t *>(dk);
         pk.out1 = static_cast<bf16_t *>(dv);
-        const int e = (d == 64) ? launch<DKDV, 64, 1, 4, 64, 80, 80, 2>(pk, s)
-                                : launch<DKDV, 128, 1, 8, 64, 144, 144, 1>(pk, s);
+        const int e = (d == 64) ? launch<DKDV, 64, 1, 4, 64, 72, 72, 2, 8>(pk, s)
+                                : launch<DKDV, 128, 1, 8, 64, 136, 136, 1, 8>(pk, s);
         if (e) return e;
     }
     if (want_dq) {           // Alg. 2: dQ (owner = query tile)
         Params pq = p;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
-        const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 80, 72, 1>(pq, s)
-                                : launch<DQ, 128, 1, 8, 64, 144, 136, 1>(pq, s);
+        const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 6>(pq, s)
+                                : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 6>(pq, s);
         if (e) return e;
     }
     return SIGATTN_OK;

@@ -7,11 +7,18 @@
 //   DKDV  (Alg. 3): owner = a tile of keys,     streamed = query/dO tiles.    Out = dK, dV
 //
 // "Owner" rows are held in registers for the whole kernel as MFMA B operands; "streamed" tiles go
-// HBM -> registers -> LDS (double buffered) and are read from LDS as MFMA A operands, either row-wise
+// HBM -> registers -> LDS (a ring of four tiles) and are read from LDS as MFMA A operands, either row-wise
 // (contraction over the head dimension) or through the transposing LDS read (contraction over tokens).
 // Every score tile is computed transposed, streamed x owner, so that the fp32 accumulator of one lane
 // holds one owner column and several streamed rows: after the fused sigmoid those registers are, without
 // any shuffle, the bf16 B operand of the next contraction over streamed tokens.
+//
+// The inner loop is a software pipeline over 32-row blocks of the streamed tensors.  One step holds, for
+// block b, the score contractions of block b + 1, the sigmoid of block b and the output contractions of
+// block b - 1.  A step is cut into slots of one MFMA each; every slot also carries an equal share of the
+// step's VALU work and, at most, the LDS read of one later A operand.  A operands travel through a small
+// ring of registers and are requested RING - 1 operands before their first use, so that no MFMA waits for
+// the LDS.  The order inside a step is pinned with scheduling fences; nothing is left to reorder.
 //
 // v_mfma_f32_32x32x16_bf16 operand layout used below (lane l, c = l % 32, g = l / 32):
 //   A[32 x 16]: lane holds row c,    k = 8 g + 0..7
@@ -21,6 +28,9 @@
 // addressed by lane (i / 4 + 4 e), 16-bit column (i % 4).  With lane r of the group pointing at
 // (row r / 4, column 4 (r % 4)) of a row-major [4 x 16] block, lane i receives column i, rows 0..3.
 #pragma once
+#ifndef SIGATTN_XP
+#define SIGATTN_XP 0   // timing experiments only: 1 no VALU, 2 no LDS operand reads, 4 no MFMA, 8 no tile streaming, 16 no barrier
+#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,7 +51,20 @@ enum Mode { FWD = 0, DQ = 1, DKDV = 2 };
 template <int V>
 struct IntC {
     static constexpr int value = V;
+    __device__ __forceinline__ constexpr int get() const { return V; }
 };
+struct DynInt {   // same interface as IntC for a value only known at run time
+    int v;
+    __device__ __forceinline__ int get() const { return v; }
+};
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 struct Params {
     const bf16_t *q, *k, *v, *d_o;   // inputs  [B, N, H, D]
@@ -73,18 +96,10 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
     return __builtin_bit_cast(unsigned, h);
 }
 
-// Registers 8 half .. 8 half + 7 of a score accumulator -> bf16 B operand (contraction slots = streamed rows).
-__device__ __forceinline__ bf16x8 acc_to_operand(const f32x16 &a, int half) {
-    u32x4 r;
-    r[0] = pack_bf16(a[8 * half + 0], a[8 * half + 1]);
-    r[1] = pack_bf16(a[8 * half + 2], a[8 * half + 3]);
-    r[2] = pack_bf16(a[8 * half + 4], a[8 * half + 5]);
-    r[3] = pack_bf16(a[8 * half + 6], a[8 * half + 7]);
-    return __builtin_bit_cast(bf16x8, r);
-}
-
-template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2>
+// Shape of one pipeline step and of the two instruction streams that are woven into it.
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int RING>
 struct Cfg {
+    static constexpr bool HAS2 = (MODE != FWD);    // a second owner tensor and a second score tile (dP)
     static constexpr int BM = NW * 32 * QB;        // owner rows per workgroup
     static constexpr int THREADS = NW * 64;
     static constexpr int KS = D / 16;              // MFMA steps over the head dimension
@@ -94,9 +109,41 @@ struct Cfg {
     static constexpr int PER = (BN * CH) / THREADS;  // chunks per thread per streamed tensor
     static constexpr int NBUF = 4;                 // LDS ring: tile t lives in slot t % 4
     static constexpr size_t LDS_BYTES = (size_t)NBUF * BN * (LD1 + LD2) * sizeof(bf16_t);
+    // A operands of one step, in the order they are used: first the row-wise ones of the score
+    // contractions (block b + 1), then the transposed ones of the output contractions (block b - 1).
+    static constexpr int NT = HAS2 ? 2 : 1;        // score tiles per block (S, dP)
+    static constexpr int NO = (MODE == DKDV) ? 2 : 1;   // output tensors
+    static constexpr int NA = KS * NT;
+    static constexpr int NC = 2 * MB * NO;
+    static constexpr int NOPS = NA + NC;
+    static constexpr int SLOTS = NOPS * QB;        // one MFMA per slot
+    // VALU work: units of two score elements (one packed bf16 register of the next B operand).
+    static constexpr int UNITS = QB * 8;
     static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
     static_assert(D % 32 == 0 && BN % 64 == 0, "tile shape (an even number of 32-row blocks per tile)");
     static_assert(LD1 % 8 == 0 && LD2 % 8 == 0 && LD1 >= D && LD2 >= D, "LDS row stride");
+    static_assert((NB * NOPS) % RING == 0 && RING >= 2 && RING <= NOPS, "operand ring does not close over a tile");
+};
+
+// The VALU instructions of one step as a flat list.  Each unit (two score elements) runs through three
+// stages -- exponentials | denominator and reciprocal | products and packing -- and the list is skewed by
+// one unit per stage, so that an instruction never follows directly on the one that feeds it.
+template <int UNITS, int OPU, int S0, int S1>
+struct ValuOrder {
+    static constexpr int LEN = UNITS * OPU;
+    int unit[LEN];
+    int op[LEN];
+    constexpr ValuOrder() : unit{}, op{} {
+        int n = 0;
+        for (int tau = 0; tau < UNITS + 2; ++tau) {
+            if (tau < UNITS)
+                for (int o = 0; o < S0; ++o) { unit[n] = tau; op[n] = o; ++n; }
+            if (tau >= 1 && tau - 1 < UNITS)
+                for (int o = S0; o < S1; ++o) { unit[n] = tau - 1; op[n] = o; ++n; }
+            if (tau >= 2 && tau - 2 < UNITS)
+                for (int o = S1; o < OPU; ++o) { unit[n] = tau - 2; op[n] = o; ++n; }
+        }
+    }
 };
 
 // Write zeros over owner rows [row0, row1) of one (z, h) slice of `out`.
@@ -117,27 +164,6 @@ __device__ __forceinline__ bf16x8 scale_bf16x8(const bf16x8 v, const float f) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) r[j] = pack_bf16((float)v[2 * j] * f, (float)v[2 * j + 1] * f);
     return __builtin_bit_cast(bf16x8, r);
-}
-
-// The fused elementwise step on one 32 x 32 score block held in MFMA accumulator layout.
-//   in : s  = t' = -(log2 e) scale <q, k>   (the factor is already inside the contraction)
-//        dp = dP (backward only);  cb = 2^(-bias log2 e)
-//   out: s  = P = sigma(x) = 1 / (1 + cb 2^t');  dp = dS = P (1 - P) dP, computed as P dP - P (P dP)
-// cb is finite and non-zero, so cb * 2^t' is 0, finite or +inf but never NaN, and P lands in [0, 1].
-// Streamed rows >= n (register i <-> row srow0 + 8 (i / 4) + i % 4) get P = 0 when MASKED.
-template <bool HAS2, bool MASKED>
-__device__ __forceinline__ void sigmoid_block(f32x16 &s, f32x16 &dp, const float cb, const int srow0, const int n) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float e = __builtin_amdgcn_exp2f(s[i]);
-        float pr = __builtin_amdgcn_rcpf(__builtin_fmaf(cb, e, 1.0f));
-        if (MASKED) pr = (srow0 + 8 * (i >> 2) + (i & 3) < n) ? pr : 0.f;
-        s[i] = pr;
-        if (HAS2) {
-            const float t1 = pr * dp[i];
-            dp[i] = __builtin_fmaf(-pr, t1, t1);
-        }
-    }
 }
 
 // Longest-first work mapping.  The launch is a 1-D grid with one workgroup per owner tile of every
@@ -205,11 +231,12 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
     }
 }
 
-template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC>
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING>
 __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
-    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2>;
-    constexpr bool HAS2 = (MODE != FWD);             // a second owner tensor and a second score tile (dP)
+    using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2, RING>;
+    constexpr bool HAS2 = C::HAS2;
     constexpr int Q2 = HAS2 ? QB : 1;
+    constexpr int NB = C::NB, NA = C::NA, NOPS = C::NOPS, SLOTS = C::SLOTS, NT = C::NT, NO = C::NO, MB = C::MB;
     constexpr float LOG2E = 1.4426950408889634f;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -247,6 +274,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     // c1 is folded into the owner operand of the score contraction (one extra bf16 rounding of that
     // operand), so t' leaves the MFMA ready for exp2; cb rides on the FMA that forms the denominator.
     // The exponent of cb is clamped to +-126 (|bias| <= 87.3 is exact; beyond that sigma is saturated).
+    // cb is finite and non-zero, so cb 2^t' is 0, finite or +inf but never NaN, and P lands in [0, 1].
     const float c1 = -p.scale * LOG2E;
     const float cb = __builtin_amdgcn_exp2f(__builtin_fminf(__builtin_fmaxf(-p.bias[z] * LOG2E, -126.0f), 126.0f));
 
@@ -271,12 +299,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         }
     }
 
-    f32x16 acc0[QB][C::MB];                        // FWD: O^T;  DQ: dQ^T;  DKDV: dK^T
-    f32x16 acc1[MODE == DKDV ? QB : 1][MODE == DKDV ? C::MB : 1];   // DKDV: dV^T
+    f32x16 acc0[QB][MB];                           // FWD: O^T;  DQ: dQ^T;  DKDV: dK^T
+    f32x16 acc1[MODE == DKDV ? QB : 1][MODE == DKDV ? MB : 1];   // DKDV: dV^T
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int mb = 0; mb < C::MB; ++mb) {
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc0[qb][mb][i] = 0.f;
             if (MODE == DKDV) {
@@ -315,92 +343,155 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     };
 
     // lane-constant pieces of the LDS addresses
-    const int rd_off1 = c * LD1 + 8 * g;           // row-wise A operand: row c, columns 16 ks + 8 g
-    const int rd_off2 = c * LD2 + 8 * g;
     const int i16 = lane & 15, g16 = (lane >> 4) & 1;
     const int tr_row = 4 * g + (i16 >> 2);         // transposed A operand: rows 4 g + 0..3 (and + 8)
     const int tr_col = 16 * g16 + 4 * (i16 & 3);   // 16 output rows (head-dim columns) per 16-lane group
-    const int tr_off1 = tr_row * LD1 + tr_col;
-    const int tr_off2 = tr_row * LD2 + tr_col;
-
-    // Stage A of a 32-row block: transposed scores t'^T[streamed 32 x owner 32] = Y1 (c1 X1)^T,
-    // and dP^T = Y2 X2^T (backward).
-    auto stage_scores = [&](const bf16_t *t1, const bf16_t *t2, f32x16 (&s)[QB], f32x16 (&dp)[Q2]) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const bf16x8 a1 = lds_read_rows(t1 + rd_off1 + 16 * ks);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], ks == 0 ? zero : s[qb], 0, 0, 0);
-            if (HAS2) {
-                const bf16x8 a2 = lds_read_rows(t2 + rd_off2 + 16 * ks);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], ks == 0 ? zero : dp[qb], 0, 0, 0);
-            }
-        }
-    };
-
-    // Stage C of a 32-row block: the contractions over its 32 streamed rows (two MFMA steps of 16), from
-    // the bf16 operands stage B left behind.
-    auto stage_outputs = [&](const bf16_t *t1, const bf16_t *t2, const bf16x8 (&pb)[QB][2], const bf16x8 (&dsb)[Q2][2]) {
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-#pragma unroll
-            for (int mb = 0; mb < C::MB; ++mb) {
-                if (MODE == FWD) {          // O^T += V^T P^T
-                    const bf16_t *a = t2 + 16 * half * LD2 + tr_off2 + 32 * mb;
-                    const bf16x8 vt = lds_read_tr(a, a + 8 * LD2);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pb[qb][half], acc0[qb][mb], 0, 0, 0);
-                } else {                    // dQ^T += K^T dS^T   |   dK^T += Q^T dS
-                    const bf16_t *a = t1 + 16 * half * LD1 + tr_off1 + 32 * mb;
-                    const bf16x8 yt = lds_read_tr(a, a + 8 * LD1);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt, dsb[qb][half], acc0[qb][mb], 0, 0, 0);
-                    if (MODE == DKDV) {     // dV^T += dO^T P
-                        const bf16_t *a2 = t2 + 16 * half * LD2 + tr_off2 + 32 * mb;
-                        const bf16x8 gt = lds_read_tr(a2, a2 + 8 * LD2);
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb)
-                            acc1[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pb[qb][half], acc1[qb][mb], 0, 0, 0);
-                    }
-                }
-            }
-        }
-    };
+    const bf16_t *rd1 = y1s + c * LD1 + 8 * g;     // row-wise A operand: row c, columns 16 ks + 8 g
+    const bf16_t *rd2 = y2s + c * LD2 + 8 * g;
+    const bf16_t *tr1 = y1s + tr_row * LD1 + tr_col;
+    const bf16_t *tr2 = y2s + tr_row * LD2 + tr_col;
 
     // Score accumulators and bf16 operands, double buffered by block parity.
     f32x16 sbuf[2][QB], dbuf[2][Q2];
-    bf16x8 pbuf[2][QB][2], dsbuf[2][Q2][2];
+    u32x4 pbuf[2][QB][2], dsbuf[2][Q2][2];
+    bf16x8 ring[RING];
 
-    // One pipeline step for the block of parity PAR.  Three independent pieces of work sit in one basic
-    // block: the score MFMAs of the NEXT block, the output MFMAs of the PREVIOUS block, and the sigmoid of
-    // THIS block on the VALU, so that the matrix pipe and the VALU can run side by side within one wave.
-    auto step = [&](auto masked_c, auto has_next_c, auto par_c, const bf16_t *n1, const bf16_t *n2,
-                    const bf16_t *p1, const bf16_t *p2, const int srow0) {
-        constexpr bool MASKED = decltype(masked_c)::value;
-        constexpr bool HAS_NEXT = decltype(has_next_c)::value;
-        constexpr int PAR = decltype(par_c)::value;
-        if (HAS_NEXT) stage_scores(n1, n2, sbuf[PAR ^ 1], dbuf[PAR ^ 1]);
-        stage_outputs(p1, p2, pbuf[PAR ^ 1], dsbuf[PAR ^ 1]);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            sigmoid_block<HAS2, MASKED>(sbuf[PAR][qb], dbuf[PAR][HAS2 ? qb : 0], cb, srow0, n);
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                pbuf[PAR][qb][half] = acc_to_operand(sbuf[PAR][qb], half);
-                if (HAS2) dsbuf[PAR][qb][half] = acc_to_operand(dbuf[PAR][qb], half);
+    // First ring row of the block `delta` blocks after block nb of the tile in ring slot `slot`.
+    auto block_row = [&](auto slot, int nb, int delta) {
+        const int nbp = nb + delta + NB;                       // >= 0 for delta >= -NB
+        const int sl = (slot.get() + nbp / NB + C::NBUF - 1) & (C::NBUF - 1);
+        return sl * BN + (nbp % NB) * 32;
+    };
+
+    // The J-th A operand counted from the start of the step on block nb of `slot` (J >= NOPS runs into the
+    // following step): row-wise operands belong to the block after the step's block, transposed ones to the
+    // block before it.
+    auto fetch = [&](auto J_, auto slot, int nb) -> bf16x8 {
+        constexpr int J = decltype(J_)::value;
+        constexpr int sstep = J / NOPS, j = J % NOPS;
+        if constexpr (j < NA) {
+            constexpr int ks = j / NT, which = j % NT;
+            const int row = block_row(slot, nb, sstep + 1);
+            if constexpr (which == 0) return lds_read_rows(rd1 + row * LD1 + 16 * ks);
+            else return lds_read_rows(rd2 + row * LD2 + 16 * ks);
+        } else {
+            constexpr int jj = j - NA, which = jj % NO, idx = jj / NO, half = idx / MB, mb = idx % MB;
+            const int row = block_row(slot, nb, sstep - 1) + 16 * half;
+            // FWD contracts V^T (tensor 2); DQ contracts K^T (tensor 1); DKDV: Q^T (1) for dK, dO^T (2) for dV
+            constexpr bool second = (MODE == FWD) || (MODE == DKDV && which == 1);
+            if constexpr (second) {
+                const bf16_t *a = tr2 + row * LD2 + 32 * mb;
+                return lds_read_tr(a, a + 8 * LD2);
+            } else {
+                const bf16_t *a = tr1 + row * LD1 + 32 * mb;
+                return lds_read_tr(a, a + 8 * LD1);
             }
         }
     };
-    using std_true = IntC<1>;
-    using std_false = IntC<0>;
 
-    // ---- prologue: tiles 0 and 1 into the ring, tile 2 into registers, scores of block 0 computed
+    // VALU work of one step: see ValuOrder.  Per unit u (registers 2w, 2w + 1 of owner block qb = u / 8):
+    //   0,1  e = 2^t'            2,3  y = 1 + cb e          4,5  P = 1 / y      [6,7  P = 0 on padded rows]
+    //   FWD : pack P
+    //   bwd : t = P dP (2 ops), dS = t - P t (2 ops), pack dS, DKDV also packs P
+    constexpr int OPU_BASE = (MODE == FWD) ? 7 : (MODE == DQ ? 11 : 12);
+
+    // One pipeline step on the block (slot, nb) of parity PAR (compile-time nb).  Slots run in program
+    // order; a scheduling fence closes each of them.
+    auto step = [&](auto masked_c, auto has_next_c, auto drain_c, auto nb_c, auto slot, const int srow0) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr bool HAS_NEXT = decltype(has_next_c)::value;
+        constexpr bool DRAIN = decltype(drain_c)::value;
+        constexpr int nb = decltype(nb_c)::value;
+        constexpr int PAR = nb & 1;
+        constexpr int G0 = (nb * NOPS) % RING;               // ring position of this step's first operand
+        constexpr int MK = MASKED ? 2 : 0;
+        constexpr int OPU = OPU_BASE + MK;
+        constexpr ValuOrder<C::UNITS, OPU, 2, 6> order{};
+        constexpr int LEN = (DRAIN || (SIGATTN_XP & 1)) ? 0 : C::UNITS * OPU;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+        static_for<0, SLOTS>([&](auto k_) {
+            constexpr int k = decltype(k_)::value;
+            constexpr int j = k / QB, qb = k % QB;
+            // ---- the MFMA of this slot
+            if constexpr (j < NA) {
+                if constexpr (HAS_NEXT && !DRAIN && !(SIGATTN_XP & 4)) {
+                    constexpr int ks = j / NT, which = j % NT;
+                    if constexpr (which == 0)
+                        sbuf[PAR ^ 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            ring[(G0 + j) % RING], xa[qb][ks], ks == 0 ? zero : sbuf[PAR ^ 1][qb], 0, 0, 0);
+                    else
+                        dbuf[PAR ^ 1][HAS2 ? qb : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            ring[(G0 + j) % RING], xb[HAS2 ? qb : 0][HAS2 ? ks : 0],
+                            ks == 0 ? zero : dbuf[PAR ^ 1][HAS2 ? qb : 0], 0, 0, 0);
+                }
+            } else {
+                constexpr int jj = j - NA, which = jj % NO, idx = jj / NO, half = idx / MB, mb = idx % MB;
+                const bf16x8 a = ring[(G0 + j) % RING];
+                if constexpr (SIGATTN_XP & 4) {
+                    asm volatile("" :: "v"(a), "v"(pbuf[PAR ^ 1][qb][half]));
+                } else if constexpr (MODE == FWD) {            // O^T += V^T P^T
+                    acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        a, __builtin_bit_cast(bf16x8, pbuf[PAR ^ 1][qb][half]), acc0[qb][mb], 0, 0, 0);
+                } else if constexpr (which == 0) {      // dQ^T += K^T dS^T   |   dK^T += Q^T dS
+                    acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        a, __builtin_bit_cast(bf16x8, dsbuf[PAR ^ 1][HAS2 ? qb : 0][half]), acc0[qb][mb], 0, 0, 0);
+                } else {                                // dV^T += dO^T P
+                    acc1[MODE == DKDV ? qb : 0][MODE == DKDV ? mb : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        a, __builtin_bit_cast(bf16x8, pbuf[PAR ^ 1][qb][half]),
+                        acc1[MODE == DKDV ? qb : 0][MODE == DKDV ? mb : 0], 0, 0, 0);
+                }
+            }
+            // ---- the register of the previous operand is free now: request the operand RING - 1 ahead
+            if constexpr (qb == 0 && (!DRAIN || j + RING - 1 < NOPS) && !(SIGATTN_XP & 2)) {
+                ring[(G0 + j + RING - 1) % RING] = fetch(IntC<j + RING - 1>{}, slot, nb);
+            }
+            // ---- this slot's share of the sigmoid
+            static_for<(k * LEN) / SLOTS, ((k + 1) * LEN) / SLOTS>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                constexpr int u = order.unit[i], o = order.op[i];
+                constexpr int uq = u / 8, w = u % 8, ra = 2 * w, rb = 2 * w + 1;
+                f32x16 &s = sbuf[PAR][uq];
+                f32x16 &dp = dbuf[PAR][HAS2 ? uq : 0];
+                if constexpr (o == 0) s[ra] = __builtin_amdgcn_exp2f(s[ra]);
+                else if constexpr (o == 1) s[rb] = __builtin_amdgcn_exp2f(s[rb]);
+                else if constexpr (o == 2) s[ra] = __builtin_fmaf(cb, s[ra], 1.0f);
+                else if constexpr (o == 3) s[rb] = __builtin_fmaf(cb, s[rb], 1.0f);
+                else if constexpr (o == 4) s[ra] = __builtin_amdgcn_rcpf(s[ra]);
+                else if constexpr (o == 5) s[rb] = __builtin_amdgcn_rcpf(s[rb]);
+                else if constexpr (MASKED && o == 6) s[ra] = (srow0 + 8 * (ra >> 2) + (ra & 3) < n) ? s[ra] : 0.f;
+                else if constexpr (MASKED && o == 7) s[rb] = (srow0 + 8 * (rb >> 2) + (rb & 3) < n) ? s[rb] : 0.f;
+                else {
+                    constexpr int e = o - 6 - MK;     // position in the mode's tail of the unit
+                    if constexpr (MODE == FWD) {
+                        pbuf[PAR][uq][w / 4][w % 4] = pack_bf16(s[ra], s[rb]);
+                    } else {
+                        if constexpr (e == 0) dp[ra] = s[ra] * dp[ra];
+                        else if constexpr (e == 1) dp[rb] = s[rb] * dp[rb];
+                        else if constexpr (e == 2) dp[ra] = __builtin_fmaf(-s[ra], dp[ra], dp[ra]);
+                        else if constexpr (e == 3) dp[rb] = __builtin_fmaf(-s[rb], dp[rb], dp[rb]);
+                        else if constexpr (e == 4) dsbuf[PAR][HAS2 ? uq : 0][w / 4][w % 4] = pack_bf16(dp[ra], dp[rb]);
+                        else pbuf[PAR][uq][w / 4][w % 4] = pack_bf16(s[ra], s[rb]);
+                    }
+                }
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    using T_ = IntC<1>;
+    using F_ = IntC<0>;
+
+    // ---- prologue: tiles 0 and 1 into the ring, tile 2 into registers, scores of block 0 computed.
+    // The step on block 0 contracts its (zero) "previous" operands with the last block of ring slot 3:
+    // that block is cleared first, so that 0 x stale LDS bits can never be 0 x NaN.
+    for (int cid = tid; cid < 32 * (LD1 / 8); cid += C::THREADS) {
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(y1s + (C::NBUF * BN - 32) * LD1 + cid * 8) = z4;
+    }
+    for (int cid = tid; cid < 32 * (LD2 / 8); cid += C::THREADS) {
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(y2s + (C::NBUF * BN - 32) * LD2 + cid * 8) = z4;
+    }
     load_tile(0);
     store_tile(0);
     if (ntiles > 1) {
@@ -410,66 +501,71 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     __syncthreads();
     load_tile(2);
 
-    stage_scores(y1s, y2s, sbuf[0], dbuf[0]);
-    {   // the "previous block" of block 0 contributes nothing: zero operands
+    {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const bf16x8 a1 = lds_read_rows(rd1 + 16 * ks);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                sbuf[0][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xa[qb][ks], ks == 0 ? zero : sbuf[0][qb], 0, 0, 0);
+            if (HAS2) {
+                const bf16x8 a2 = lds_read_rows(rd2 + 16 * ks);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    dbuf[0][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[qb][ks], ks == 0 ? zero : dbuf[0][qb], 0, 0, 0);
+            }
+        }
         const u32x4 z4 = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                pbuf[1][qb][half] = __builtin_bit_cast(bf16x8, z4);
-                if (HAS2) dsbuf[1][qb][half] = __builtin_bit_cast(bf16x8, z4);
+                pbuf[1][qb][half] = z4;
+                if (HAS2) dsbuf[1][qb][half] = z4;
             }
     }
+    // operands 0 .. RING - 2 of the first step
+    static_for<0, RING - 1>([&](auto J_) { ring[decltype(J_)::value % RING] = fetch(J_, IntC<0>{}, 0); });
 
-    // ---- main loop over all tiles but the last: no padded rows, every block has a successor
-    int slot = 0;                                    // t % NBUF
-    const bf16_t *prev1 = y1s, *prev2 = y2s;         // block whose output contractions are still due
-    for (int t = 0; t + 1 < ntiles; ++t) {
-        const int slot_next = (slot + 1) & (C::NBUF - 1);
-        const bf16_t *t1 = y1s + slot * BN * LD1;
-        const bf16_t *t2 = y2s + slot * BN * LD2;
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-            const bf16_t *n1 = (nb + 1 < C::NB) ? t1 + (nb + 1) * 32 * LD1 : y1s + slot_next * BN * LD1;
-            const bf16_t *n2 = (nb + 1 < C::NB) ? t2 + (nb + 1) * 32 * LD2 : y2s + slot_next * BN * LD2;
-            const int srow0 = t * BN + nb * 32 + 4 * g;
-            if (nb & 1) step(std_false{}, std_true{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
-            else        step(std_false{}, std_true{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
-            prev1 = t1 + nb * 32 * LD1;
-            prev2 = t2 + nb * 32 * LD2;
-        }
-        // tile t + 2 goes to slot (t + 2) % 4 = (t - 2) % 4, last read during tile t - 1 (as the previous
-        // block of its first step); every wave passed the barrier that ended tile t - 1.  It becomes
-        // visible at this barrier, a full tile before its first read at the end of tile t + 1.
+    // ---- main loop over all tiles but the last: no padded rows, every block has a successor.  The loop is
+    // unrolled over the four ring slots so that every LDS address is a lane constant plus an immediate.
+    auto tile_body = [&](auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        static_for<0, NB>([&](auto nb_) { step(F_{}, T_{}, F_{}, nb_, slot_c, 0); });
+        // tile t + 2 goes to slot (t + 2) % 4 = (t - 2) % 4, last read during the first step of tile t - 1
+        // (as the previous block); every wave passed the barrier that ended tile t - 1.  It becomes
+        // visible at this barrier, most of a tile before its first read near the end of tile t + 1.
         // (Past the end these are harmless: the registers then hold zeros and the slot is not live.)
-        store_tile((slot + 2) & (C::NBUF - 1));
-        __syncthreads();
-        load_tile(t + 3);
-        slot = slot_next;
+        if (!(SIGATTN_XP & 8)) store_tile((slot + 2) & (C::NBUF - 1));
+        if (!(SIGATTN_XP & 16)) __syncthreads();
+    };
+    int t = 0;
+    const int last = ntiles - 1;
+    int slot_rt = 0;
+    while (true) {
+        if (t >= last) { slot_rt = 0; break; }
+        tile_body(IntC<0>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        if (t >= last) { slot_rt = 1; break; }
+        tile_body(IntC<1>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        if (t >= last) { slot_rt = 2; break; }
+        tile_body(IntC<2>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        if (t >= last) { slot_rt = 3; break; }
+        tile_body(IntC<3>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
     }
 
-    // ---- last tile: rows >= n masked, the final block has no successor
+    // ---- last tile: rows >= n masked, its final block has no successor; then the output contractions
+    // of that final block (a step that only drains).
     {
-        const int t = ntiles - 1;
-        const bf16_t *t1 = y1s + slot * BN * LD1;
-        const bf16_t *t2 = y2s + slot * BN * LD2;
-#pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-            const bf16_t *n1 = t1 + (nb + 1) * 32 * LD1;
-            const bf16_t *n2 = t2 + (nb + 1) * 32 * LD2;
-            const int srow0 = t * BN + nb * 32 + 4 * g;
-            if (nb + 1 < C::NB) {
-                if (nb & 1) step(std_true{}, std_true{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
-                else        step(std_true{}, std_true{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
-            } else {
-                if (nb & 1) step(std_true{}, std_false{}, IntC<1>{}, n1, n2, prev1, prev2, srow0);
-                else        step(std_true{}, std_false{}, IntC<0>{}, n1, n2, prev1, prev2, srow0);
-            }
-            prev1 = t1 + nb * 32 * LD1;
-            prev2 = t2 + nb * 32 * LD2;
-        }
-        stage_outputs(prev1, prev2, pbuf[(C::NB - 1) & 1], dsbuf[(C::NB - 1) & 1]);
+        const DynInt slot{slot_rt};
+        static_for<0, NB>([&](auto nb_) {
+            constexpr int nb = decltype(nb_)::value;
+            const int srow0 = last * BN + nb * 32 + 4 * g;
+            if constexpr (nb + 1 < NB) step(T_{}, T_{}, F_{}, nb_, slot, srow0);
+            else step(T_{}, F_{}, F_{}, nb_, slot, srow0);
+        });
+        const DynInt slot_next{(slot_rt + 1) & (C::NBUF - 1)};
+        step(F_{}, F_{}, T_{}, IntC<0>{}, slot_next, 0);
     }
 
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
@@ -482,7 +578,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         const bool ok = r < n;                                       // padded owner rows are written as zero
         const size_t off = slice + (size_t)r * row_stride + 4 * g;
 #pragma unroll
-        for (int mb = 0; mb < C::MB; ++mb) {
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 u32x2 w0 = {0u, 0u};
