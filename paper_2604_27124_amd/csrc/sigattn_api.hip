@@ -14,6 +14,7 @@ int check_shape(int B, int N, int H, int d) {
     if (d != 64 && d != 128) return SIGATTN_ERR_UNSUPPORTED_D;
     if ((long long)B * H > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;     // grid.x limit
     if ((long long)B * N * H * d >= (1LL << 40)) return SIGATTN_ERR_TOO_LARGE;
+    if ((long long)H * d > (1LL << 20)) return SIGATTN_ERR_TOO_LARGE;      // 32-bit lane offsets within one streamed tile
     return SIGATTN_OK;
 }
 
@@ -110,7 +111,7 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
         Params pk = p;
         pk.out0 = static_cast<bf16_t *>(dk);
         pk.out1 = static_cast<bf16_t *>(dv);
-        const int e = (d == 64) ? launch<DKDV, 64, 1, 4, 64, 72, 72, 2, 8>(pk, s)
+        const int e = (d == 64) ? launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s)
                                 : launch<DKDV, 128, 1, 8, 64, 136, 136, 1, 8>(pk, s);
         if (e) return e;
     }
@@ -118,7 +119,7 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
         Params pq = p;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
-        const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 6>(pq, s)
+        const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4>(pq, s)
                                 : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 6>(pq, s);
         if (e) return e;
     }

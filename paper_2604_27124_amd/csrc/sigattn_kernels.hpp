@@ -28,9 +28,6 @@
 // addressed by lane (i / 4 + 4 e), 16-bit column (i % 4).  With lane r of the group pointing at
 // (row r / 4, column 4 (r % 4)) of a row-major [4 x 16] block, lane i receives column i, rows 0..3.
 #pragma once
-#ifndef SIGATTN_XP
-#define SIGATTN_XP 0   // timing experiments only: 1 no VALU, 2 no LDS operand reads, 4 no MFMA, 8 no tile streaming, 16 no barrier
-#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -331,6 +328,27 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             st2[it] = ok ? b : z4;
         }
     };
+    // Tiles that lie wholly below the valid length need neither the clamp nor the zero fill: their
+    // addresses are a uniform base (scalar registers, advanced per tile) plus a lane constant.
+    unsigned ld_off[C::PER];
+#pragma unroll
+    for (int it = 0; it < C::PER; ++it) {
+        const int cid = tid + it * C::THREADS;
+        ld_off[it] = (unsigned)(cid / C::CH) * (unsigned)row_stride + (unsigned)(cid % C::CH) * 8u;
+    }
+    auto load_full_tile = [&](int t) {
+        const bf16_t *b1 = y1 + slice + (size_t)t * BN * row_stride;
+        const bf16_t *b2 = y2 + slice + (size_t)t * BN * row_stride;
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) {
+            st1[it] = *reinterpret_cast<const u32x4 *>(b1 + ld_off[it]);
+            st2[it] = *reinterpret_cast<const u32x4 *>(b2 + ld_off[it]);
+        }
+    };
+    auto load_next = [&](int t) {   // t * BN + BN <= n exactly when t < ntiles - 1
+        if (t < ntiles - 1) load_full_tile(t);
+        else load_tile(t);
+    };
     auto store_tile = [&](int slot) {
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
@@ -397,8 +415,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
 
     // One pipeline step on the block (slot, nb) of parity PAR (compile-time nb).  Slots run in program
     // order; a scheduling fence closes each of them.
-    auto step = [&](auto masked_c, auto has_next_c, auto drain_c, auto nb_c, auto slot, const int srow0) {
+    auto step = [&](auto masked_c, auto has_next_c, auto drain_c, auto nb_c, auto slot, const int srow0,
+                    auto store_at_c, const int store_slot) {
         constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr int STORE_AT = decltype(store_at_c)::value;   // slot before which the staged tile goes to LDS (-1: never)
         constexpr bool HAS_NEXT = decltype(has_next_c)::value;
         constexpr bool DRAIN = decltype(drain_c)::value;
         constexpr int nb = decltype(nb_c)::value;
@@ -407,15 +427,19 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         constexpr int MK = MASKED ? 2 : 0;
         constexpr int OPU = OPU_BASE + MK;
         constexpr ValuOrder<C::UNITS, OPU, 2, 6> order{};
-        constexpr int LEN = (DRAIN || (SIGATTN_XP & 1)) ? 0 : C::UNITS * OPU;
+        constexpr int LEN = DRAIN ? 0 : C::UNITS * OPU;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
         static_for<0, SLOTS>([&](auto k_) {
             constexpr int k = decltype(k_)::value;
             constexpr int j = k / QB, qb = k % QB;
+            if constexpr (k == STORE_AT) {
+                store_tile(store_slot);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // ---- the MFMA of this slot
             if constexpr (j < NA) {
-                if constexpr (HAS_NEXT && !DRAIN && !(SIGATTN_XP & 4)) {
+                if constexpr (HAS_NEXT && !DRAIN) {
                     constexpr int ks = j / NT, which = j % NT;
                     if constexpr (which == 0)
                         sbuf[PAR ^ 1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -428,9 +452,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             } else {
                 constexpr int jj = j - NA, which = jj % NO, idx = jj / NO, half = idx / MB, mb = idx % MB;
                 const bf16x8 a = ring[(G0 + j) % RING];
-                if constexpr (SIGATTN_XP & 4) {
-                    asm volatile("" :: "v"(a), "v"(pbuf[PAR ^ 1][qb][half]));
-                } else if constexpr (MODE == FWD) {            // O^T += V^T P^T
+                if constexpr (MODE == FWD) {            // O^T += V^T P^T
                     acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         a, __builtin_bit_cast(bf16x8, pbuf[PAR ^ 1][qb][half]), acc0[qb][mb], 0, 0, 0);
                 } else if constexpr (which == 0) {      // dQ^T += K^T dS^T   |   dK^T += Q^T dS
@@ -443,7 +465,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                 }
             }
             // ---- the register of the previous operand is free now: request the operand RING - 1 ahead
-            if constexpr (qb == 0 && (!DRAIN || j + RING - 1 < NOPS) && !(SIGATTN_XP & 2)) {
+            if constexpr (qb == 0 && (!DRAIN || j + RING - 1 < NOPS)) {
                 ring[(G0 + j + RING - 1) % RING] = fetch(IntC<j + RING - 1>{}, slot, nb);
             }
             // ---- this slot's share of the sigmoid
@@ -530,28 +552,48 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
 
     // ---- main loop over all tiles but the last: no padded rows, every block has a successor.  The loop is
     // unrolled over the four ring slots so that every LDS address is a lane constant plus an immediate.
+    // Tile t + 2 goes to slot (t + 2) % 4 = (t - 2) % 4, last read during the first step of tile t - 1 (as
+    // the previous block); every wave passed the barrier that ended tile t - 1.  The staged registers are
+    // written half-way through the last step of tile t, and the barrier that ends the tile waits only until
+    // those writes have left the LDS queue: LDS operations of a wave complete in order, so it is enough to
+    // let the READS_AFTER operand reads issued behind them stay in flight.  The tile becomes visible at
+    // that barrier, most of a tile before its first read near the end of tile t + 1.
+    // (Past the end the writes are harmless: the registers then hold zeros and the slot is not live.)
+    constexpr auto reads_from = [](int first_slot) {
+        int cnt = 0;
+        for (int k = first_slot; k < SLOTS; k += QB) {
+            const int j = (k / QB + RING - 1) % NOPS;
+            cnt += (j < NA) ? 1 : 2;           // one 16-byte read, or two transposing 8-byte reads
+        }
+        return cnt;
+    };
+    constexpr int STORE_AT = [&] {             // about half-way, later if too many reads would follow
+        int k = (SLOTS / 2 / QB) * QB;
+        while (reads_from(k) > 12) k += QB;
+        return k;
+    }();
+    constexpr int READS_AFTER = reads_from(STORE_AT);
+    static_assert(READS_AFTER <= 15 && STORE_AT < SLOTS, "more reads behind the tile store than the LDS counter can express");
     auto tile_body = [&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
-        static_for<0, NB>([&](auto nb_) { step(F_{}, T_{}, F_{}, nb_, slot_c, 0); });
-        // tile t + 2 goes to slot (t + 2) % 4 = (t - 2) % 4, last read during the first step of tile t - 1
-        // (as the previous block); every wave passed the barrier that ended tile t - 1.  It becomes
-        // visible at this barrier, most of a tile before its first read near the end of tile t + 1.
-        // (Past the end these are harmless: the registers then hold zeros and the slot is not live.)
-        if (!(SIGATTN_XP & 8)) store_tile((slot + 2) & (C::NBUF - 1));
-        if (!(SIGATTN_XP & 16)) __syncthreads();
+        static_for<0, NB>([&](auto nb_) {
+            if constexpr (decltype(nb_)::value + 1 < NB) step(F_{}, T_{}, F_{}, nb_, slot_c, 0, IntC<-1>{}, 0);
+            else step(F_{}, T_{}, F_{}, nb_, slot_c, 0, IntC<STORE_AT>{}, (slot + 2) & (C::NBUF - 1));
+        });
+        asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(READS_AFTER) : "memory");
     };
     int t = 0;
     const int last = ntiles - 1;
     int slot_rt = 0;
     while (true) {
         if (t >= last) { slot_rt = 0; break; }
-        tile_body(IntC<0>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        tile_body(IntC<0>{}); load_next(t + 3); ++t;
         if (t >= last) { slot_rt = 1; break; }
-        tile_body(IntC<1>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        tile_body(IntC<1>{}); load_next(t + 3); ++t;
         if (t >= last) { slot_rt = 2; break; }
-        tile_body(IntC<2>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        tile_body(IntC<2>{}); load_next(t + 3); ++t;
         if (t >= last) { slot_rt = 3; break; }
-        tile_body(IntC<3>{}); if (!(SIGATTN_XP & 8)) load_tile(t + 3); ++t;
+        tile_body(IntC<3>{}); load_next(t + 3); ++t;
     }
 
     // ---- last tile: rows >= n masked, its final block has no successor; then the output contractions
@@ -561,11 +603,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         static_for<0, NB>([&](auto nb_) {
             constexpr int nb = decltype(nb_)::value;
             const int srow0 = last * BN + nb * 32 + 4 * g;
-            if constexpr (nb + 1 < NB) step(T_{}, T_{}, F_{}, nb_, slot, srow0);
-            else step(T_{}, F_{}, F_{}, nb_, slot, srow0);
+            if constexpr (nb + 1 < NB) step(T_{}, T_{}, F_{}, nb_, slot, srow0, IntC<-1>{}, 0);
+            else step(T_{}, F_{}, F_{}, nb_, slot, srow0, IntC<-1>{}, 0);
         });
         const DynInt slot_next{(slot_rt + 1) & (C::NBUF - 1)};
-        step(F_{}, F_{}, T_{}, IntC<0>{}, slot_next, 0);
+        step(F_{}, F_{}, T_{}, IntC<0>{}, slot_next, 0, IntC<-1>{}, 0);
     }
 
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
