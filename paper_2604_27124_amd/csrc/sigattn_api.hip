@@ -108,19 +108,36 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     if (want_dkdv) {         // Alg. 3: dK, dV (owner = key tile)
-        Params pk = p;
-        pk.out0 = static_cast<bf16_t *>(dk);
-        pk.out1 = static_cast<bf16_t *>(dv);
-        const int e = (d == 64) ? launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s)
-                                : launch<DKDV, 128, 1, 8, 64, 136, 136, 1, 8>(pk, s);
-        if (e) return e;
+        if (d == 64) {
+            Params pk = p;
+            pk.out0 = static_cast<bf16_t *>(dk);
+            pk.out1 = static_cast<bf16_t *>(dv);
+            const int e = launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s);
+            if (e) return e;
+        } else {
+            // At d = 128 the accumulators of dK and dV together do not fit the register file next to the
+            // pipeline, so the two halves of Alg. 3 run as the other two kernels with the roles of queries
+            // and keys exchanged (P is the same number seen from either side):
+            //   dV_j = sum_i P_ij dO_i            is the forward pass with (Q, K, V)     := (K, Q, dO)
+            //   dK_j = scale sum_i dS_ij q_i      is the dQ pass with      (Q, dO, K, V) := (K, V, Q, dO)
+            Params pv = p;
+            pv.q = p.k; pv.k = p.q; pv.v = p.d_o; pv.d_o = nullptr;
+            pv.out0 = static_cast<bf16_t *>(dv);
+            int e = launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(pv, s);
+            if (e) return e;
+            Params pk = p;
+            pk.q = p.k; pk.d_o = p.v; pk.k = p.q; pk.v = p.d_o;
+            pk.out0 = static_cast<bf16_t *>(dk);
+            e = launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pk, s);
+            if (e) return e;
+        }
     }
     if (want_dq) {           // Alg. 2: dQ (owner = query tile)
         Params pq = p;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
         const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4>(pq, s)
-                                : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 6>(pq, s);
+                                : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pq, s);
         if (e) return e;
     }
     return SIGATTN_OK;
