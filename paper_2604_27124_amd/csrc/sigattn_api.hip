@@ -81,7 +81,13 @@ int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
     p.scale = scale;
     p.B = B; p.N = N_max; p.H = H;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (d == 64) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
+    if (d == 64) {
+        // 512-row owner tiles (two owner blocks per wave) feed two MFMAs from every LDS operand read and win
+        // on long sequences; 256-row tiles need half the registers, so two workgroups share a CU, and they
+        // halve the granularity of the grid: measured better up to N_max = 4096 (the host sees N_max only).
+        if (N_max > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
+        return launch<FWD, 64, 1, 8, 64, 72, 72, 1, 4>(p, s);
+    }
     return launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(p, s);
 }
 

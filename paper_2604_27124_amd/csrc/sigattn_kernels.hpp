@@ -514,14 +514,28 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         const u32x4 z4 = {0u, 0u, 0u, 0u};
         *reinterpret_cast<u32x4 *>(y2s + (C::NBUF * BN - 32) * LD2 + cid * 8) = z4;
     }
-    load_tile(0);
-    store_tile(0);
-    if (ntiles > 1) {
+    {   // the first three tiles are requested back to back, so their latencies overlap
+        load_tile(0);
+        u32x4 a1[C::PER], a2[C::PER];
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) { a1[it] = st1[it]; a2[it] = st2[it]; }
         load_tile(1);
-        store_tile(1);
+        u32x4 b1[C::PER], b2[C::PER];
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) { b1[it] = st1[it]; b2[it] = st2[it]; }
+        load_tile(2);
+#pragma unroll
+        for (int it = 0; it < C::PER; ++it) {
+            const int cid = tid + it * C::THREADS;
+            const int r = cid / C::CH;
+            const int col = (cid % C::CH) * 8;
+            *reinterpret_cast<u32x4 *>(y1s + r * LD1 + col) = a1[it];
+            *reinterpret_cast<u32x4 *>(y2s + r * LD2 + col) = a2[it];
+            *reinterpret_cast<u32x4 *>(y1s + (BN + r) * LD1 + col) = b1[it];
+            *reinterpret_cast<u32x4 *>(y2s + (BN + r) * LD2 + col) = b2[it];
+        }
     }
     __syncthreads();
-    load_tile(2);
 
     {
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
