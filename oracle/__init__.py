@@ -13,4 +13,6 @@ from .sigmoid_attn_oracle import (  # noqa: F401
     bwd_q_rows,
     bwd_kv_rows,
     valid_flops,
+    cross_fwd,
+    cross_bwd,
 )

@@ -208,3 +208,106 @@ void sigattn_oracle_matrices(const float *q, const float *k, const float *v, con
         }
     }
 }
+
+/*
+ * ---------------------------------------------------------------------------
+ * Separate query and key lengths, and the gradient of the bias.
+ *
+ * Appendix Alg. 1-3 are written for q in [Z, L_q, H, D] and k, v in
+ * [Z, L_k, H, D] with valid lengths n_q and n_k of their own; Sec. 3 allows
+ * the bias b to be learnable.  Same definition as above with i < n_q, j < n_k:
+ *
+ *   O_i  = sum_{j<n_k} P_ij v_j      (i < n_q; 0 for i >= n_q, and 0 when n_k = 0)
+ *   dV_j = sum_{i<n_q} P_ij dO_i,  dK_j = scale sum_{i<n_q} dS_ij q_i   (j < n_k)
+ *   dQ_i = scale sum_{j<n_k} dS_ij k_j                                  (i < n_q)
+ *   db_z = sum_h sum_{i<n_q} sum_{j<n_k} dS_ij      (x_ij = scale s_ij + b_z, so dx_ij/db_z = 1)
+ *
+ * Plain loops again; nothing is shared with the functions above except sigma()
+ * and the index helper.  db may be NULL.
+ * ---------------------------------------------------------------------------
+ */
+void sigattn_oracle_cross_fwd(const float *q, const float *k, const float *v, double *o,
+                              const int32_t *seqlens_q, const int32_t *seqlens_k, const double *bias,
+                              double scale, int B, int Lq, int Lk, int H, int d)
+{
+    for (int z = 0; z < B; ++z) {
+        const int nq = valid_len(seqlens_q, z, Lq), nk = valid_len(seqlens_k, z, Lk);
+        for (int h = 0; h < H; ++h) {
+#pragma omp parallel for schedule(dynamic, 8)
+            for (int i = 0; i < Lq; ++i) {
+                double *oi = o + at(z, i, h, Lq, H, d);
+                for (int c = 0; c < d; ++c) oi[c] = 0.0;
+                if (i >= nq) continue;
+                const float *qi = q + at(z, i, h, Lq, H, d);
+                for (int j = 0; j < nk; ++j) {
+                    const float *kj = k + at(z, j, h, Lk, H, d);
+                    const float *vj = v + at(z, j, h, Lk, H, d);
+                    double s = 0.0;
+                    for (int c = 0; c < d; ++c) s += (double)qi[c] * (double)kj[c];
+                    const double p = sigma(scale * s + bias[z]);
+                    for (int c = 0; c < d; ++c) oi[c] += p * (double)vj[c];
+                }
+            }
+        }
+    }
+}
+
+void sigattn_oracle_cross_bwd(const float *q, const float *k, const float *v, const float *d_o,
+                              double *dq, double *dk, double *dv, double *db,
+                              const int32_t *seqlens_q, const int32_t *seqlens_k, const double *bias,
+                              double scale, int B, int Lq, int Lk, int H, int d)
+{
+    for (int z = 0; z < B; ++z) {
+        const int nq = valid_len(seqlens_q, z, Lq), nk = valid_len(seqlens_k, z, Lk);
+        double dbz = 0.0;
+        for (int h = 0; h < H; ++h) {
+            /* dQ and the bias gradient: one query row at a time. */
+            double dbh = 0.0;
+#pragma omp parallel for schedule(dynamic, 8) reduction(+ : dbh)
+            for (int i = 0; i < Lq; ++i) {
+                double *dqi = dq + at(z, i, h, Lq, H, d);
+                for (int c = 0; c < d; ++c) dqi[c] = 0.0;
+                if (i >= nq) continue;
+                const float *qi = q + at(z, i, h, Lq, H, d);
+                const float *doi = d_o + at(z, i, h, Lq, H, d);
+                for (int j = 0; j < nk; ++j) {
+                    const float *kj = k + at(z, j, h, Lk, H, d);
+                    const float *vj = v + at(z, j, h, Lk, H, d);
+                    double s = 0.0, dp = 0.0;
+                    for (int c = 0; c < d; ++c) s += (double)qi[c] * (double)kj[c];
+                    for (int c = 0; c < d; ++c) dp += (double)doi[c] * (double)vj[c];
+                    const double x = scale * s + bias[z];
+                    const double ds = sigma(x) * sigma(-x) * dp;
+                    dbh += ds;
+                    for (int c = 0; c < d; ++c) dqi[c] += ds * (double)kj[c];
+                }
+                for (int c = 0; c < d; ++c) dqi[c] *= scale;
+            }
+            dbz += dbh;
+            /* dK, dV: one key row at a time. */
+#pragma omp parallel for schedule(dynamic, 8)
+            for (int j = 0; j < Lk; ++j) {
+                double *dkj = dk + at(z, j, h, Lk, H, d);
+                double *dvj = dv + at(z, j, h, Lk, H, d);
+                for (int c = 0; c < d; ++c) { dkj[c] = 0.0; dvj[c] = 0.0; }
+                if (j >= nk) continue;
+                const float *kj = k + at(z, j, h, Lk, H, d);
+                const float *vj = v + at(z, j, h, Lk, H, d);
+                for (int i = 0; i < nq; ++i) {
+                    const float *qi = q + at(z, i, h, Lq, H, d);
+                    const float *doi = d_o + at(z, i, h, Lq, H, d);
+                    double s = 0.0, dp = 0.0;
+                    for (int c = 0; c < d; ++c) s += (double)qi[c] * (double)kj[c];
+                    for (int c = 0; c < d; ++c) dp += (double)doi[c] * (double)vj[c];
+                    const double x = scale * s + bias[z];
+                    const double p = sigma(x);
+                    const double ds = p * sigma(-x) * dp;
+                    for (int c = 0; c < d; ++c) dvj[c] += p * (double)doi[c];
+                    for (int c = 0; c < d; ++c) dkj[c] += ds * (double)qi[c];
+                }
+                for (int c = 0; c < d; ++c) dkj[c] *= scale;
+            }
+        }
+        if (db) db[z] = dbz;
+    }
+}

@@ -59,6 +59,10 @@ def _load():
         lib.sigattn_oracle_bwd.restype = None
         lib.sigattn_oracle_matrices.argtypes = [_F, _F, _F, _F, _D, _D, _D, _I, _D, cd, ci, ci, ci, ci, ci, ci]
         lib.sigattn_oracle_matrices.restype = None
+        lib.sigattn_oracle_cross_fwd.argtypes = [_F, _F, _F, _D, _I, _I, _D, cd, ci, ci, ci, ci, ci]
+        lib.sigattn_oracle_cross_fwd.restype = None
+        lib.sigattn_oracle_cross_bwd.argtypes = [_F, _F, _F, _F, _D, _D, _D, _D, _I, _I, _D, cd, ci, ci, ci, ci, ci]
+        lib.sigattn_oracle_cross_bwd.restype = None
         _lib = lib
     return _lib
 
@@ -148,6 +152,46 @@ def matrices(q, k, v, d_o, seqlens, bias, scale: float, z: int, h: int):
     lib.sigattn_oracle_matrices(_p(q, _F), _p(k, _F), _p(v, _F), _p(d_o, _F), _p(p, _D), _p(dp, _D), _p(ds, _D),
                                 _p(seqlens, _I), _p(bias, _D), float(scale), B, N, H, d, int(z), int(h))
     return p, dp, ds
+
+
+def _cross_common(q, k, v, seqlens_q, seqlens_k, bias):
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    if k.shape != v.shape or q.shape[0] != k.shape[0] or q.shape[2:] != k.shape[2:]:
+        raise ValueError("q is [B, L_q, H, d]; k and v are [B, L_k, H, d]")
+    B, Lq, H, d = q.shape
+    Lk = k.shape[1]
+    seqlens_q = np.ascontiguousarray(seqlens_q, dtype=np.int32)
+    seqlens_k = np.ascontiguousarray(seqlens_k, dtype=np.int32)
+    bias = np.ascontiguousarray(bias, dtype=np.float64)
+    if seqlens_q.shape != (B,) or seqlens_k.shape != (B,) or bias.shape != (B,):
+        raise ValueError("seqlens_q, seqlens_k and bias must have shape [B]")
+    return q, k, v, seqlens_q, seqlens_k, bias, (B, Lq, Lk, H, d)
+
+
+def cross_fwd(q, k, v, seqlens_q, seqlens_k, bias, scale: float) -> np.ndarray:
+    """O [B, L_q, H, d] with separate query and key lengths (appendix Alg. 1 as printed)."""
+    q, k, v, sq, sk, bias, (B, Lq, Lk, H, d) = _cross_common(q, k, v, seqlens_q, seqlens_k, bias)
+    o = np.zeros((B, Lq, H, d), dtype=np.float64)
+    _load().sigattn_oracle_cross_fwd(_p(q, _F), _p(k, _F), _p(v, _F), _p(o, _D), _p(sq, _I), _p(sk, _I),
+                                     _p(bias, _D), float(scale), B, Lq, Lk, H, d)
+    return o
+
+
+def cross_bwd(q, k, v, d_o, seqlens_q, seqlens_k, bias, scale: float):
+    """(dQ [B,L_q,H,d], dK, dV [B,L_k,H,d], db [B]) with separate lengths (Alg. 2, Alg. 3; db: Sec. 3's
+    learnable bias, db_z = sum over heads and valid pairs of dS)."""
+    q, k, v, sq, sk, bias, (B, Lq, Lk, H, d) = _cross_common(q, k, v, seqlens_q, seqlens_k, bias)
+    d_o = _f32(d_o)
+    if d_o.shape != q.shape:
+        raise ValueError("d_o must have the shape of q")
+    dq = np.zeros((B, Lq, H, d), dtype=np.float64)
+    dk = np.zeros((B, Lk, H, d), dtype=np.float64)
+    dv = np.zeros_like(dk)
+    db = np.zeros((B,), dtype=np.float64)
+    _load().sigattn_oracle_cross_bwd(_p(q, _F), _p(k, _F), _p(v, _F), _p(d_o, _F), _p(dq, _D), _p(dk, _D),
+                                     _p(dv, _D), _p(db, _D), _p(sq, _I), _p(sk, _I), _p(bias, _D), float(scale),
+                                     B, Lq, Lk, H, d)
+    return dq, dk, dv, db
 
 
 # ----------------------------------------------------------------------------------------------
