@@ -94,6 +94,24 @@ int sigmoid_attn_bwd_dkdv(const void *q, const void *k, const void *v, const voi
                           const int32_t *seqlens, const float *bias, float scale,
                           int B, int N_max, int H, int d, void *stream);
 
+/*
+ * Separate query and key lengths (appendix Alg. 1-3 are printed with L_q, L_k and n_q, n_k of their own).
+ *   q, o, d_o, dq : device bf16 [B, L_q, H, d]        k, v, dk, dv : device bf16 [B, L_k, H, d]
+ *   seqlens_q, seqlens_k : device int32 [B]; valid queries are rows [0, seqlens_q[z]), valid keys rows
+ *                          [0, seqlens_k[z]); values outside [0, L] are clamped inside the kernels
+ *   O_i = sum_{j < n_k} sigma(scale <q_i, k_j> + bias[z]) v_j for i < n_q, else 0 (also 0 when n_k = 0);
+ *   dQ over j < n_k; dK, dV over i < n_q; padded rows of every output are written as 0.
+ * Everything else (layout, ownership, stream, errors) as for the self-attention entry points, which
+ * are these with L_q = L_k and seqlens_q = seqlens_k.  No workspace is needed.
+ */
+int sigmoid_attn_cross_fwd(const void *q, const void *k, const void *v, void *o,
+                           const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                           int B, int L_q, int L_k, int H, int d, void *stream);
+int sigmoid_attn_cross_bwd(const void *q, const void *k, const void *v, const void *d_o,
+                           void *dq, void *dk, void *dv,
+                           const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                           int B, int L_q, int L_k, int H, int d, void *stream);
+
 /* Scratch bytes sigmoid_attn_bwd needs for this shape (0 on invalid shapes). */
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d);
 

@@ -22,7 +22,8 @@ SIGATTN_ERR_LAUNCH = -5
 SIGATTN_ERR_TOO_LARGE = -6
 
 EXPORTS = ("sigmoid_attn_version", "sigmoid_attn_strerror", "sigmoid_attn_fwd", "sigmoid_attn_bwd",
-           "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes")
+           "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes",
+           "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd")
 
 _lib = None
 
@@ -54,6 +55,10 @@ def load() -> ctypes.CDLL:
         lib.sigmoid_attn_bwd_dq.restype = ci
         lib.sigmoid_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, vp]
         lib.sigmoid_attn_bwd_dkdv.restype = ci
+        lib.sigmoid_attn_cross_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, ci, vp]
+        lib.sigmoid_attn_cross_fwd.restype = ci
+        lib.sigmoid_attn_cross_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, ci, vp]
+        lib.sigmoid_attn_cross_bwd.restype = ci
         lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
         _lib = lib
@@ -176,3 +181,56 @@ def sigmoid_attn_bwd_dkdv(q, k, v, d_o, seqlens, bias, scale: float, dk=None, dv
     if rc != SIGATTN_OK:
         raise SigAttnError(rc)
     return dk, dv
+
+
+def _check_cross(q, k, v):
+    _check(q, "q")
+    _check(k, "k")
+    _check(v, "v", k.shape)
+    if q.shape[0] != k.shape[0] or q.shape[2:] != k.shape[2:]:
+        raise ValueError("q is [B, L_q, H, d]; k and v are [B, L_k, H, d]")
+
+
+def sigmoid_attn_cross_fwd(q, k, v, seqlens_q, seqlens_k, bias, scale: float, out=None, stream=None):
+    """Forward pass with separate query and key lengths: q [B, L_q, H, d]; k, v [B, L_k, H, d]."""
+    import torch
+    _check_cross(q, k, v)
+    B, Lq, H, d = q.shape
+    Lk = k.shape[1]
+    _check_vec(seqlens_q, "seqlens_q", B, torch.int32)
+    _check_vec(seqlens_k, "seqlens_k", B, torch.int32)
+    _check_vec(bias, "bias", B, torch.float32)
+    if out is None:
+        out = torch.empty_like(q)
+    _check(out, "out", q.shape)
+    rc = load().sigmoid_attn_cross_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                       seqlens_q.data_ptr(), seqlens_k.data_ptr(), bias.data_ptr(), float(scale),
+                                       B, Lq, Lk, H, d, _stream_ptr(stream))
+    if rc != SIGATTN_OK:
+        raise SigAttnError(rc)
+    return out
+
+
+def sigmoid_attn_cross_bwd(q, k, v, d_o, seqlens_q, seqlens_k, bias, scale: float, dq=None, dk=None, dv=None,
+                           stream=None) -> Tuple:
+    """(dQ [B, L_q, H, d], dK, dV [B, L_k, H, d]) with separate query and key lengths."""
+    import torch
+    _check_cross(q, k, v)
+    _check(d_o, "d_o", q.shape)
+    B, Lq, H, d = q.shape
+    Lk = k.shape[1]
+    _check_vec(seqlens_q, "seqlens_q", B, torch.int32)
+    _check_vec(seqlens_k, "seqlens_k", B, torch.int32)
+    _check_vec(bias, "bias", B, torch.float32)
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(k) if dv is None else dv
+    _check(dq, "dq", q.shape)
+    _check(dk, "dk", k.shape)
+    _check(dv, "dv", k.shape)
+    rc = load().sigmoid_attn_cross_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
+                                       dk.data_ptr(), dv.data_ptr(), seqlens_q.data_ptr(), seqlens_k.data_ptr(),
+                                       bias.data_ptr(), float(scale), B, Lq, Lk, H, d, _stream_ptr(stream))
+    if rc != SIGATTN_OK:
+        raise SigAttnError(rc)
+    return dq, dk, dv

@@ -62,11 +62,14 @@ size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d) {
     return 0;   // the backward pass owns each output tile exclusively: no scratch, no atomics
 }
 
-int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
-                     const int32_t *seqlens, const float *bias, float scale,
-                     int B, int N_max, int H, int d, void *stream) {
-    if (!q || !k || !v || !o || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
-    if (int e = check_shape(B, N_max, H, d)) return e;
+// ---- common implementations: separate query-side and key-side lengths (self-attention passes them twice)
+
+static int fwd_impl(const void *q, const void *k, const void *v, void *o,
+                    const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                    int B, int L_q, int L_k, int H, int d, void *stream) {
+    if (!q || !k || !v || !o || !seqlens_q || !seqlens_k || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, L_q, H, d)) return e;
+    if (int e = check_shape(B, L_k, H, d)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SIGATTN_ERR_MISALIGNED;
 
     Params p{};
@@ -76,28 +79,31 @@ int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
     p.d_o = nullptr;
     p.out0 = static_cast<bf16_t *>(o);
     p.out1 = nullptr;
-    p.seqlens = seqlens;
+    p.seqlens = seqlens_q;          // owner side: queries
+    p.seqlens_str = seqlens_k;      // streamed side: keys / values
     p.bias = bias;
     p.scale = scale;
-    p.B = B; p.N = N_max; p.H = H;
+    p.B = B; p.N = L_q; p.N_str = L_k; p.H = H;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d == 64) {
         // 512-row owner tiles (two owner blocks per wave) feed two MFMAs from every LDS operand read and win
         // on long sequences; 256-row tiles need half the registers, so two workgroups share a CU, and they
-        // halve the granularity of the grid: measured better up to N_max = 4096 (the host sees N_max only).
-        if (N_max > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
+        // halve the granularity of the grid: measured better up to 4096 streamed rows (the host sees the
+        // padded lengths only).
+        if (L_k > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
         return launch<FWD, 64, 1, 8, 64, 72, 72, 1, 4>(p, s);
     }
     return launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(p, s);
 }
 
-static int bwd_common(const void *q, const void *k, const void *v, const void *d_o,
-                      void *dq, void *dk, void *dv,
-                      const int32_t *seqlens, const float *bias, float scale,
-                      int B, int N_max, int H, int d, void *stream, bool want_dq, bool want_dkdv) {
-    if (!q || !k || !v || !d_o || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+static int bwd_impl(const void *q, const void *k, const void *v, const void *d_o,
+                    void *dq, void *dk, void *dv,
+                    const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                    int B, int L_q, int L_k, int H, int d, void *stream, bool want_dq, bool want_dkdv) {
+    if (!q || !k || !v || !d_o || !seqlens_q || !seqlens_k || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
     if ((want_dq && !dq) || (want_dkdv && (!dk || !dv))) return SIGATTN_ERR_INVALID_ARG;
-    if (int e = check_shape(B, N_max, H, d)) return e;
+    if (int e = check_shape(B, L_q, H, d)) return e;
+    if (int e = check_shape(B, L_k, H, d)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o)) return SIGATTN_ERR_MISALIGNED;
     if ((want_dq && !aligned16(dq)) || (want_dkdv && (!aligned16(dk) || !aligned16(dv))))
         return SIGATTN_ERR_MISALIGNED;
@@ -107,15 +113,16 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
     p.k = static_cast<const bf16_t *>(k);
     p.v = static_cast<const bf16_t *>(v);
     p.d_o = static_cast<const bf16_t *>(d_o);
-    p.seqlens = seqlens;
     p.bias = bias;
     p.scale = scale;
-    p.B = B; p.N = N_max; p.H = H;
+    p.B = B; p.H = H;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (want_dkdv) {         // Alg. 3: dK, dV (owner = key tile)
+    if (want_dkdv) {         // Alg. 3: dK, dV (owner = key tile, streamed = queries and dO)
+        Params pk = p;
+        pk.seqlens = seqlens_k; pk.N = L_k;
+        pk.seqlens_str = seqlens_q; pk.N_str = L_q;
         if (d == 64) {
-            Params pk = p;
             pk.out0 = static_cast<bf16_t *>(dk);
             pk.out1 = static_cast<bf16_t *>(dv);
             const int e = launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s);
@@ -126,20 +133,22 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
             // and keys exchanged (P is the same number seen from either side):
             //   dV_j = sum_i P_ij dO_i            is the forward pass with (Q, K, V)     := (K, Q, dO)
             //   dK_j = scale sum_i dS_ij q_i      is the dQ pass with      (Q, dO, K, V) := (K, V, Q, dO)
-            Params pv = p;
+            Params pv = pk;
             pv.q = p.k; pv.k = p.q; pv.v = p.d_o; pv.d_o = nullptr;
             pv.out0 = static_cast<bf16_t *>(dv);
             int e = launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(pv, s);
             if (e) return e;
-            Params pk = p;
-            pk.q = p.k; pk.d_o = p.v; pk.k = p.q; pk.v = p.d_o;
-            pk.out0 = static_cast<bf16_t *>(dk);
-            e = launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pk, s);
+            Params pd = pk;
+            pd.q = p.k; pd.d_o = p.v; pd.k = p.q; pd.v = p.d_o;
+            pd.out0 = static_cast<bf16_t *>(dk);
+            e = launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pd, s);
             if (e) return e;
         }
     }
-    if (want_dq) {           // Alg. 2: dQ (owner = query tile)
+    if (want_dq) {           // Alg. 2: dQ (owner = query tile, streamed = keys and values)
         Params pq = p;
+        pq.seqlens = seqlens_q; pq.N = L_q;
+        pq.seqlens_str = seqlens_k; pq.N_str = L_k;
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
         const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4>(pq, s)
@@ -149,29 +158,49 @@ static int bwd_common(const void *q, const void *k, const void *v, const void *d
     return SIGATTN_OK;
 }
 
+int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
+                     const int32_t *seqlens, const float *bias, float scale,
+                     int B, int N_max, int H, int d, void *stream) {
+    return fwd_impl(q, k, v, o, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, stream);
+}
+
 int sigmoid_attn_bwd(const void *q, const void *k, const void *v, const void *d_o,
                      void *dq, void *dk, void *dv,
                      const int32_t *seqlens, const float *bias, float scale,
                      int B, int N_max, int H, int d,
                      void *workspace, size_t workspace_bytes, void *stream) {
     if (!dq || !dk || !dv) return SIGATTN_ERR_INVALID_ARG;
-    const int e0 = bwd_common(q, k, v, d_o, dq, dk, dv, seqlens, bias, scale, B, N_max, H, d, nullptr, false, false);
+    const int e0 = bwd_impl(q, k, v, d_o, dq, dk, dv, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, nullptr, false, false);
     if (e0) return e0;       // argument errors first, as the header orders them
     const size_t need = sigmoid_attn_bwd_workspace_bytes(B, N_max, H, d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return SIGATTN_ERR_WORKSPACE;
-    return bwd_common(q, k, v, d_o, dq, dk, dv, seqlens, bias, scale, B, N_max, H, d, stream, true, true);
+    return bwd_impl(q, k, v, d_o, dq, dk, dv, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, stream, true, true);
 }
 
 int sigmoid_attn_bwd_dq(const void *q, const void *k, const void *v, const void *d_o, void *dq,
                         const int32_t *seqlens, const float *bias, float scale,
                         int B, int N_max, int H, int d, void *stream) {
-    return bwd_common(q, k, v, d_o, dq, nullptr, nullptr, seqlens, bias, scale, B, N_max, H, d, stream, true, false);
+    return bwd_impl(q, k, v, d_o, dq, nullptr, nullptr, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, stream, true, false);
 }
 
 int sigmoid_attn_bwd_dkdv(const void *q, const void *k, const void *v, const void *d_o, void *dk, void *dv,
                           const int32_t *seqlens, const float *bias, float scale,
                           int B, int N_max, int H, int d, void *stream) {
-    return bwd_common(q, k, v, d_o, nullptr, dk, dv, seqlens, bias, scale, B, N_max, H, d, stream, false, true);
+    return bwd_impl(q, k, v, d_o, nullptr, dk, dv, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, stream, false, true);
+}
+
+int sigmoid_attn_cross_fwd(const void *q, const void *k, const void *v, void *o,
+                           const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                           int B, int L_q, int L_k, int H, int d, void *stream) {
+    return fwd_impl(q, k, v, o, seqlens_q, seqlens_k, bias, scale, B, L_q, L_k, H, d, stream);
+}
+
+int sigmoid_attn_cross_bwd(const void *q, const void *k, const void *v, const void *d_o,
+                           void *dq, void *dk, void *dv,
+                           const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                           int B, int L_q, int L_k, int H, int d, void *stream) {
+    if (!dq || !dk || !dv) return SIGATTN_ERR_INVALID_ARG;
+    return bwd_impl(q, k, v, d_o, dq, dk, dv, seqlens_q, seqlens_k, bias, scale, B, L_q, L_k, H, d, stream, true, true);
 }
 
 }  // extern "C"

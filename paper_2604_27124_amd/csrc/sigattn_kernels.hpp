@@ -63,14 +63,19 @@ __device__ __forceinline__ void static_for(F &&f) {
     }
 }
 
+// Owner side = the tensors whose rows a workgroup keeps (queries in FWD and DQ, keys in DKDV); streamed side
+// = the other one.  The two sides have padded lengths and valid lengths of their own (appendix Alg. 1-3:
+// L_q, L_k, n_q, n_k); self-attention passes the same numbers twice.
 struct Params {
-    const bf16_t *q, *k, *v, *d_o;   // inputs  [B, N, H, D]
+    const bf16_t *q, *k, *v, *d_o;   // inputs: q, d_o [B, L_q, H, D];  k, v [B, L_k, H, D]
     bf16_t *out0;                    // FWD: O;  DQ: dQ;  DKDV: dK
     bf16_t *out1;                    // DKDV: dV
-    const int32_t *seqlens;          // [B]
+    const int32_t *seqlens;          // [B] valid lengths of the owner side
+    const int32_t *seqlens_str;      // [B] valid lengths of the streamed side
     const float *bias;               // [B]
     float scale;
-    int B, N, H;
+    int B, N, H;                     // N: padded length of the owner side
+    int N_str;                       // padded length of the streamed side
 };
 
 #define SIGATTN_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
@@ -249,9 +254,14 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     m0 = __builtin_amdgcn_readfirstlane(m0);
     const int m1 = (m0 + C::BM < p.N) ? m0 + C::BM : p.N;
     const size_t row_stride = (size_t)p.H * D;
-    const size_t slice = ((size_t)z * p.N * p.H + h) * D;           // element offset of row 0 of (z, h)
+    const size_t slice = ((size_t)z * p.N * p.H + h) * D;           // owner side: element offset of row 0 of (z, h)
+    const size_t slice_s = ((size_t)z * p.N_str * p.H + h) * D;     // streamed side
+    int ns = p.seqlens_str[z];                                      // valid rows of the streamed side
+    ns = ns < 0 ? 0 : (ns > p.N_str ? p.N_str : ns);
+    ns = __builtin_amdgcn_readfirstlane(ns);
 
-    if (m0 >= n) {   // wholly padded owner tile: write zeros, do nothing else (block-sparse early exit)
+    // Wholly padded owner tile, or nothing to stream: write zeros, do nothing else (block-sparse early exit).
+    if (m0 >= n || ns == 0) {
         zero_rows<D, C::THREADS>(p.out0, slice, row_stride, m0, m1);
         if (MODE == DKDV) zero_rows<D, C::THREADS>(p.out1, slice, row_stride, m0, m1);
         return;
@@ -311,7 +321,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         }
 
     // ---- streamed tile movement: HBM -> registers -> LDS ring slot
-    const int ntiles = (n + BN - 1) / BN;
+    const int ntiles = (ns + BN - 1) / BN;
     u32x4 st1[C::PER], st2[C::PER];
     auto load_tile = [&](int t) {   // branch-free: rows beyond the valid length read a clamped row, then become 0
 #pragma unroll
@@ -319,8 +329,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             const int cid = tid + it * C::THREADS;
             const int r = t * BN + cid / C::CH;
             const int col = (cid % C::CH) * 8;
-            const bool ok = r < n;
-            const size_t off = slice + (size_t)(ok ? r : n - 1) * row_stride + col;
+            const bool ok = r < ns;
+            const size_t off = slice_s + (size_t)(ok ? r : ns - 1) * row_stride + col;
             const u32x4 a = *reinterpret_cast<const u32x4 *>(y1 + off);
             const u32x4 b = *reinterpret_cast<const u32x4 *>(y2 + off);
             const u32x4 z4 = {0u, 0u, 0u, 0u};
@@ -337,15 +347,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         ld_off[it] = (unsigned)(cid / C::CH) * (unsigned)row_stride + (unsigned)(cid % C::CH) * 8u;
     }
     auto load_full_tile = [&](int t) {
-        const bf16_t *b1 = y1 + slice + (size_t)t * BN * row_stride;
-        const bf16_t *b2 = y2 + slice + (size_t)t * BN * row_stride;
+        const bf16_t *b1 = y1 + slice_s + (size_t)t * BN * row_stride;
+        const bf16_t *b2 = y2 + slice_s + (size_t)t * BN * row_stride;
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
             st1[it] = *reinterpret_cast<const u32x4 *>(b1 + ld_off[it]);
             st2[it] = *reinterpret_cast<const u32x4 *>(b2 + ld_off[it]);
         }
     };
-    auto load_next = [&](int t) {   // t * BN + BN <= n exactly when t < ntiles - 1
+    auto load_next = [&](int t) {   // t * BN + BN <= ns exactly when t < ntiles - 1
         if (t < ntiles - 1) load_full_tile(t);
         else load_tile(t);
     };
@@ -481,8 +491,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                 else if constexpr (o == 3) s[rb] = __builtin_fmaf(cb, s[rb], 1.0f);
                 else if constexpr (o == 4) s[ra] = __builtin_amdgcn_rcpf(s[ra]);
                 else if constexpr (o == 5) s[rb] = __builtin_amdgcn_rcpf(s[rb]);
-                else if constexpr (MASKED && o == 6) s[ra] = (srow0 + 8 * (ra >> 2) + (ra & 3) < n) ? s[ra] : 0.f;
-                else if constexpr (MASKED && o == 7) s[rb] = (srow0 + 8 * (rb >> 2) + (rb & 3) < n) ? s[rb] : 0.f;
+                else if constexpr (MASKED && o == 6) s[ra] = (srow0 + 8 * (ra >> 2) + (ra & 3) < ns) ? s[ra] : 0.f;
+                else if constexpr (MASKED && o == 7) s[rb] = (srow0 + 8 * (rb >> 2) + (rb & 3) < ns) ? s[rb] : 0.f;
                 else {
                     constexpr int e = o - 6 - MK;     // position in the mode's tail of the unit
                     if constexpr (MODE == FWD) {

@@ -75,6 +75,28 @@ def test_bwd_argument_validation(lib):
     assert B.sigmoid_attn_bwd_workspace_bytes(2, 256, 2, 96) == 0
 
 
+def test_cross_argument_validation(lib):
+    p = 4096
+
+    def fwd(q=p, k=p, v=p, o=p, sq=p, sk=p, b=p, scale=0.125, Bn=2, Lq=128, Lk=300, H=2, d=64):
+        return lib.sigmoid_attn_cross_fwd(q, k, v, o, sq, sk, b, scale, Bn, Lq, Lk, H, d, None)
+
+    def bwd(q=p, k=p, v=p, g=p, dq=p, dk=p, dv=p, sq=p, sk=p, b=p, scale=0.125, Bn=2, Lq=128, Lk=300, H=2, d=128):
+        return lib.sigmoid_attn_cross_bwd(q, k, v, g, dq, dk, dv, sq, sk, b, scale, Bn, Lq, Lk, H, d, None)
+
+    assert fwd(sk=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(Lk=0) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(Lq=-1) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(d=32) == B.SIGATTN_ERR_UNSUPPORTED_D
+    assert fwd(o=p + 8) == B.SIGATTN_ERR_MISALIGNED
+    assert fwd(scale=float("inf")) == B.SIGATTN_ERR_INVALID_ARG
+    assert fwd(H=1 << 15, d=128) == B.SIGATTN_ERR_TOO_LARGE
+    assert bwd(sq=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(dk=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(Lk=0) == B.SIGATTN_ERR_INVALID_ARG
+    assert bwd(dv=p + 2) == B.SIGATTN_ERR_MISALIGNED
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 8, 1, 64, dtype=torch.bfloat16)
