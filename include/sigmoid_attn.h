@@ -112,6 +112,22 @@ int sigmoid_attn_cross_bwd(const void *q, const void *k, const void *v, const vo
                            const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
                            int B, int L_q, int L_k, int H, int d, void *stream);
 
+/*
+ * dQ together with the gradient of the bias (Sec. 3 allows a learnable b; x_ij = scale s_ij + b_z, hence
+ * db_z = sum over heads and valid pairs of dS_ij).  The sum rides on the dQ kernel (Alg. 2).
+ *   dq        : out, device bf16 [B, N_max, H, d] as for sigmoid_attn_bwd_dq
+ *   dbias     : out, device float [B]; fully overwritten (0 for an empty sequence)
+ *   workspace : device scratch of at least sigmoid_attn_bwd_dq_dbias_workspace_bytes(...) bytes, 16-byte
+ *               aligned, owned by the caller; contents irrelevant on entry, undefined on exit
+ * The summation order is fixed: results are bitwise reproducible.  nwg = B * H * ceil(N_max / 256)
+ * must be below 2^31 (SIGATTN_ERR_TOO_LARGE).
+ */
+size_t sigmoid_attn_bwd_dq_dbias_workspace_bytes(int B, int N_max, int H, int d);
+int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq, float *dbias,
+                              const int32_t *seqlens, const float *bias, float scale,
+                              int B, int N_max, int H, int d,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Scratch bytes sigmoid_attn_bwd needs for this shape (0 on invalid shapes). */
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d);
 

@@ -23,7 +23,8 @@ SIGATTN_ERR_TOO_LARGE = -6
 
 EXPORTS = ("sigmoid_attn_version", "sigmoid_attn_strerror", "sigmoid_attn_fwd", "sigmoid_attn_bwd",
            "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes",
-           "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd")
+           "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd",
+           "sigmoid_attn_bwd_dq_dbias", "sigmoid_attn_bwd_dq_dbias_workspace_bytes")
 
 _lib = None
 
@@ -59,6 +60,10 @@ def load() -> ctypes.CDLL:
         lib.sigmoid_attn_cross_fwd.restype = ci
         lib.sigmoid_attn_cross_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, ci, vp]
         lib.sigmoid_attn_cross_bwd.restype = ci
+        lib.sigmoid_attn_bwd_dq_dbias.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, vp, sz, vp]
+        lib.sigmoid_attn_bwd_dq_dbias.restype = ci
+        lib.sigmoid_attn_bwd_dq_dbias_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        lib.sigmoid_attn_bwd_dq_dbias_workspace_bytes.restype = sz
         lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
         _lib = lib
@@ -234,3 +239,33 @@ def sigmoid_attn_cross_bwd(q, k, v, d_o, seqlens_q, seqlens_k, bias, scale: floa
     if rc != SIGATTN_OK:
         raise SigAttnError(rc)
     return dq, dk, dv
+
+
+def sigmoid_attn_bwd_dq_dbias_workspace_bytes(B: int, N_max: int, H: int, d: int) -> int:
+    return int(load().sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, N_max, H, d))
+
+
+def sigmoid_attn_bwd_dq_dbias(q, k, v, d_o, seqlens, bias, scale: float, dq=None, dbias=None, workspace=None,
+                              stream=None):
+    """(dQ, dbias [B] float32): the query gradient together with the gradient of the per-sequence bias."""
+    import torch
+    _check(q, "q")
+    for t, name in ((k, "k"), (v, "v"), (d_o, "d_o")):
+        _check(t, name, q.shape)
+    B, N, H, d = q.shape
+    _check_vec(seqlens, "seqlens", B, torch.int32)
+    _check_vec(bias, "bias", B, torch.float32)
+    dq = torch.empty_like(q) if dq is None else dq
+    _check(dq, "dq", q.shape)
+    dbias = torch.empty(B, dtype=torch.float32, device=q.device) if dbias is None else dbias
+    _check_vec(dbias, "dbias", B, torch.float32)
+    need = sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, N, H, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    rc = load().sigmoid_attn_bwd_dq_dbias(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
+                                          dbias.data_ptr(), seqlens.data_ptr(), bias.data_ptr(), float(scale),
+                                          B, N, H, d, workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SIGATTN_OK:
+        raise SigAttnError(rc)
+    return dq, dbias

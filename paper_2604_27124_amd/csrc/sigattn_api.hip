@@ -20,7 +20,7 @@ int check_shape(int B, int N, int H, int d) {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING>
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING, bool WITH_DB = false>
 int launch(const Params &p, hipStream_t stream) {
     using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2, RING>;
     const long long tiles = ((long long)p.N + C::BM - 1) / C::BM;
@@ -28,7 +28,7 @@ int launch(const Params &p, hipStream_t stream) {
     if (wgs > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;
     dim3 grid((unsigned)wgs, 1, 1);
     dim3 block(C::THREADS, 1, 1);
-    auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC, RING>;
+    auto kern = sigattn_kernel<MODE, D, QB, NW, BN, LD1, LD2, OCC, RING, WITH_DB>;
     if (C::LDS_BYTES > 65536) {   // more dynamic LDS than the default limit: opt in (idempotent, host-side only)
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)C::LDS_BYTES) != hipSuccess)
@@ -91,7 +91,7 @@ static int fwd_impl(const void *q, const void *k, const void *v, void *o,
         // halve the granularity of the grid: measured better up to 4096 streamed rows (the host sees the
         // padded lengths only).
         if (L_k > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
-        return launch<FWD, 64, 1, 8, 64, 72, 72, 1, 4>(p, s);
+        return launch<FWD, 64, 1, 8, 64, 72, 72, 4, 4>(p, s);
     }
     return launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(p, s);
 }
@@ -187,6 +187,46 @@ int sigmoid_attn_bwd_dkdv(const void *q, const void *k, const void *v, const voi
                           const int32_t *seqlens, const float *bias, float scale,
                           int B, int N_max, int H, int d, void *stream) {
     return bwd_impl(q, k, v, d_o, nullptr, dk, dv, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d, stream, false, true);
+}
+
+// dQ workgroups own 256 query rows at either head dimension: one partial per workgroup.
+static long long dq_workgroups(int B, int N, int H) { return (((long long)N + 255) / 256) * B * H; }
+
+size_t sigmoid_attn_bwd_dq_dbias_workspace_bytes(int B, int N_max, int H, int d) {
+    if (check_shape(B, N_max, H, d) != SIGATTN_OK) return 0;
+    return (size_t)dq_workgroups(B, N_max, H) * (sizeof(float) + sizeof(int32_t));
+}
+
+int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq, float *dbias,
+                              const int32_t *seqlens, const float *bias, float scale,
+                              int B, int N_max, int H, int d,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    if (!q || !k || !v || !d_o || !dq || !dbias || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, N_max, H, d)) return e;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq)) return SIGATTN_ERR_MISALIGNED;
+    const size_t need = sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, N_max, H, d);
+    if (!workspace || workspace_bytes < need) return SIGATTN_ERR_WORKSPACE;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(dbias) & 3u)) return SIGATTN_ERR_MISALIGNED;
+
+    const long long nwg = dq_workgroups(B, N_max, H);
+    Params p{};
+    p.q = static_cast<const bf16_t *>(q);
+    p.k = static_cast<const bf16_t *>(k);
+    p.v = static_cast<const bf16_t *>(v);
+    p.d_o = static_cast<const bf16_t *>(d_o);
+    p.out0 = static_cast<bf16_t *>(dq);
+    p.seqlens = seqlens; p.seqlens_str = seqlens;
+    p.bias = bias;
+    p.scale = scale;
+    p.B = B; p.N = N_max; p.N_str = N_max; p.H = H;
+    p.db_part = static_cast<float *>(workspace);
+    p.db_seq = reinterpret_cast<int32_t *>(p.db_part + nwg);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4, true>(p, s)
+                            : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2, true>(p, s);
+    if (e) return e;
+    hipLaunchKernelGGL(sigattn_db_reduce, dim3((unsigned)B), dim3(256), 0, s, p.db_part, p.db_seq, (int)nwg, dbias);
+    return hipGetLastError() == hipSuccess ? SIGATTN_OK : SIGATTN_ERR_LAUNCH;
 }
 
 int sigmoid_attn_cross_fwd(const void *q, const void *k, const void *v, void *o,

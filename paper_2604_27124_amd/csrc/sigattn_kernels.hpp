@@ -76,6 +76,8 @@ struct Params {
     float scale;
     int B, N, H;                     // N: padded length of the owner side
     int N_str;                       // padded length of the streamed side
+    float *db_part;                  // DQ with bias gradient: per-workgroup partial sums [gridDim.x]
+    int32_t *db_seq;                 //   and the sequence each workgroup belongs to [gridDim.x]
 };
 
 #define SIGATTN_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
@@ -233,8 +235,9 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
     }
 }
 
-template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING>
+template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING, bool WITH_DB = false>
 __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
+    static_assert(!WITH_DB || MODE == DQ, "the bias gradient rides on the dQ kernel");
     using C = Cfg<MODE, D, QB, NW, BN, LD1, LD2, RING>;
     constexpr bool HAS2 = C::HAS2;
     constexpr int Q2 = HAS2 ? QB : 1;
@@ -264,6 +267,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     if (m0 >= n || ns == 0) {
         zero_rows<D, C::THREADS>(p.out0, slice, row_stride, m0, m1);
         if (MODE == DKDV) zero_rows<D, C::THREADS>(p.out1, slice, row_stride, m0, m1);
+        if (WITH_DB && threadIdx.x == 0) {
+            p.db_part[blockIdx.x] = 0.f;
+            p.db_seq[blockIdx.x] = z;
+        }
         return;
     }
 
@@ -319,6 +326,19 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                 for (int i = 0; i < 16; ++i) acc1[qb][mb][i] = 0.f;
             }
         }
+
+    // Bias gradient db = sum of dS over all valid pairs: one more MFMA per 16 streamed rows with an all-ones
+    // A operand puts the column sums of dS^T (the bf16 values that also feed dQ) into every row of accdb.
+    f32x16 accdb[WITH_DB ? QB : 1];
+    bf16x8 ones;
+    if (WITH_DB) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) accdb[qb][i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ones[i] = (bf16_t)1.0f;
+    }
 
     // ---- streamed tile movement: HBM -> registers -> LDS ring slot
     const int ntiles = (ns + BN - 1) / BN;
@@ -468,6 +488,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                 } else if constexpr (which == 0) {      // dQ^T += K^T dS^T   |   dK^T += Q^T dS
                     acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         a, __builtin_bit_cast(bf16x8, dsbuf[PAR ^ 1][HAS2 ? qb : 0][half]), acc0[qb][mb], 0, 0, 0);
+                    if constexpr (WITH_DB && mb == MB - 1)
+                        accdb[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            ones, __builtin_bit_cast(bf16x8, dsbuf[PAR ^ 1][HAS2 ? qb : 0][half]), accdb[qb], 0, 0, 0);
                 } else {                                // dV^T += dO^T P
                     acc1[MODE == DKDV ? qb : 0][MODE == DKDV ? mb : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         a, __builtin_bit_cast(bf16x8, pbuf[PAR ^ 1][qb][half]),
@@ -634,6 +657,28 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         step(F_{}, F_{}, T_{}, IntC<0>{}, slot_next, 0, IntC<-1>{}, 0);
     }
 
+    if constexpr (WITH_DB) {
+        // Row 0 of accdb (register 0 of the lanes with g = 0) holds, per owner row, the sum of dS over all
+        // streamed rows.  Owner rows beyond the valid length carry dO = 0, hence dS = 0.  Fixed-order sums:
+        // lanes by butterfly, waves through LDS, workgroups in a second kernel.
+        float v = 0.f;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) v += accdb[qb][0];
+        v = (g == 0) ? v : 0.f;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        __shared__ float s_db[NW];
+        if (lane == 0) s_db[wave] = v;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) t += s_db[w];
+            p.db_part[blockIdx.x] = t;
+            p.db_seq[blockIdx.x] = z;
+        }
+    }
+
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
     // register i holds head-dim column 32 mb + 8 (i/4) + 4 g + (i%4): four consecutive columns per store.
     const float oscale = (MODE == FWD) ? 1.0f : p.scale;            // dQ and dK carry the factor `scale`
@@ -664,6 +709,23 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             }
         }
     }
+}
+
+// Second stage of the bias gradient: db[z] = sum of the partials of the workgroups of sequence z, in a
+// fixed order (thread t takes workgroups t, t + 256, ...; then a tree in LDS), so the result is
+// bitwise reproducible.  One workgroup per sequence.
+__global__ void __launch_bounds__(256) sigattn_db_reduce(const float *part, const int32_t *seq, int nwg, float *db) {
+    __shared__ float s[256];
+    const int z = blockIdx.x;
+    float t = 0.f;
+    for (int i = threadIdx.x; i < nwg; i += 256) t += (seq[i] == z) ? part[i] : 0.f;
+    s[threadIdx.x] = t;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) s[threadIdx.x] += s[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) db[z] = s[0];
 }
 
 }  // namespace sigattn

@@ -97,6 +97,26 @@ def test_cross_argument_validation(lib):
     assert bwd(dv=p + 2) == B.SIGATTN_ERR_MISALIGNED
 
 
+def test_dq_dbias_argument_validation(lib):
+    p = 4096
+    need = B.sigmoid_attn_bwd_dq_dbias_workspace_bytes(2, 300, 3, 64)
+    assert need == 2 * 3 * 2 * 8          # one (float, int32) pair per 256-row query tile of every (z, h)
+    assert B.sigmoid_attn_bwd_dq_dbias_workspace_bytes(2, 300, 3, 100) == 0
+
+    def f(q=p, g=p, dq=p, db=p, ws=p, wsb=need, d=64, Bn=2):
+        return lib.sigmoid_attn_bwd_dq_dbias(q, p, p, g, dq, db, p, p, 0.125, Bn, 300, 3, d, ws, wsb, None)
+
+    assert f(db=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert f(g=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert f(Bn=0) == B.SIGATTN_ERR_INVALID_ARG
+    assert f(d=96) == B.SIGATTN_ERR_UNSUPPORTED_D
+    assert f(dq=p + 2) == B.SIGATTN_ERR_MISALIGNED
+    assert f(ws=None) == B.SIGATTN_ERR_WORKSPACE
+    assert f(wsb=need - 1) == B.SIGATTN_ERR_WORKSPACE
+    assert f(ws=p + 4) == B.SIGATTN_ERR_MISALIGNED
+    assert f(db=p + 2) == B.SIGATTN_ERR_MISALIGNED
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 8, 1, 64, dtype=torch.bfloat16)
