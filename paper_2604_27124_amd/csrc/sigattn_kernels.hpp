@@ -182,10 +182,13 @@ template <int BM, int THREADS>
 __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n, int &m0) {
     __shared__ int s_len[MAP_MAX_B];      // clamped valid length, by batch index
     __shared__ int s_seq[MAP_MAX_B];      // batch index, by rank (longest first)
+    __shared__ int s_res[4];              // z, n, h, m0 of this workgroup
     const int T = (p.N + BM - 1) / BM;    // owner tiles per (z, h), padded ones included
     const int id = blockIdx.x;
-    const bool sorted = p.B <= MAP_MAX_B;
-    if (sorted) {
+    if (p.B <= MAP_MAX_B) {
+        // Ranked lists: valid tiles by rank (longest sequence first), then padded tiles by batch index.
+        // One thread per sequence sums the tile counts in front of its own (independent LDS reads, no
+        // dependent chain) and the one whose range holds this workgroup's id publishes the answer.
         for (int t = threadIdx.x; t < p.B; t += THREADS) {
             const int v = p.seqlens[t];
             s_len[t] = v < 0 ? 0 : (v > p.N ? p.N : v);
@@ -201,18 +204,45 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
             s_seq[rank] = t;
         }
         __syncthreads();
+        for (int r = threadIdx.x; r < p.B; r += THREADS) {
+            int before_valid = 0, before_padded = 0, all_valid = 0;
+            for (int u = 0; u < p.B; ++u) {
+                const int tiles_ranked = (s_len[s_seq[u]] + BM - 1) / BM;     // valid tiles of the sequence of rank u
+                const int tiles_batch = (s_len[u] + BM - 1) / BM;             // valid tiles of sequence u
+                all_valid += tiles_ranked;
+                before_valid += (u < r) ? tiles_ranked : 0;
+                before_padded += (u < r) ? (T - tiles_batch) : 0;
+            }
+            {   // valid tiles of the sequence of rank r
+                const int b = s_seq[r], len = s_len[b];
+                const int lo = before_valid * p.H, cnt = ((len + BM - 1) / BM) * p.H;
+                if (id >= lo && id < lo + cnt) {
+                    const int rest = id - lo;
+                    s_res[0] = b; s_res[1] = len; s_res[2] = rest % p.H; s_res[3] = (rest / p.H) * BM;
+                }
+            }
+            {   // padded tiles of sequence r (batch order)
+                const int len = s_len[r], first = (len + BM - 1) / BM;
+                const int lo = (all_valid + before_padded) * p.H, cnt = (T - first) * p.H;
+                if (id >= lo && id < lo + cnt) {
+                    const int rest = id - lo;
+                    s_res[0] = r; s_res[1] = len; s_res[2] = rest % p.H; s_res[3] = (first + rest / p.H) * BM;
+                }
+            }
+        }
+        __syncthreads();
+        z = s_res[0]; n = s_res[1]; h = s_res[2]; m0 = s_res[3];
+        return;
     }
+    // More sequences than the LDS lists hold: batch order, valid tiles first, then the padded ones.
     auto len_of = [&](int b) {
-        if (sorted) return s_len[b];
         const int v = p.seqlens[b];
         return v < 0 ? 0 : (v > p.N ? p.N : v);
     };
-    // valid tiles, longest sequence first; then the padded tiles
     int rest = id;
     bool found = false;
     z = 0; h = 0; n = 0; m0 = 0;
-    for (int r = 0; r < p.B && !found; ++r) {
-        const int b = sorted ? s_seq[r] : r;
+    for (int b = 0; b < p.B && !found; ++b) {
         const int len = len_of(b);
         const int cnt = ((len + BM - 1) / BM) * p.H;
         if (rest < cnt) {
@@ -304,7 +334,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         for (int ks = 0; ks < C::KS; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (ok) t = *reinterpret_cast<const u32x4 *>(x1 + off + 16 * ks);
-            xa[qb][ks] = scale_bf16x8(__builtin_bit_cast(bf16x8, t), c1);
+            xa[qb][ks] = __builtin_bit_cast(bf16x8, t);      // scaled by c1 once the streamed tiles are requested
             if (HAS2) {
                 u32x4 t2 = {0u, 0u, 0u, 0u};
                 if (ok) t2 = *reinterpret_cast<const u32x4 *>(x2 + off + 16 * ks);
@@ -557,6 +587,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) { b1[it] = st1[it]; b2[it] = st2[it]; }
         load_tile(2);
+        // every request of the prologue is in flight now; the owner rows, requested first, arrive first
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) xa[qb][ks] = scale_bf16x8(xa[qb][ks], c1);
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
             const int cid = tid + it * C::THREADS;
