@@ -59,6 +59,7 @@ def main() -> int:
     ap.add_argument("--workload", default="long")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
@@ -135,6 +136,14 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, w.seed, names[dom]))},
         "context": PAPER_CONTEXT,
     }
+    if not args.no_mfma_ceiling:
+        # the matrix cores alone, same process, same box: nominal rate on constant operands, power-limited
+        # sustained rate on random ones (the latter is what any bf16 contraction on real data lives under)
+        rnd = binding.sigmoid_attn_diag_mfma_tflops("random")
+        cst = binding.sigmoid_attn_diag_mfma_tflops("constant")
+        out["mfma_ceiling"] = {"random_operands_tflops": round(rnd, 1), "constant_operands_tflops": round(cst, 1),
+                               "value_over_random_ceiling": round(tflops / rnd, 4),
+                               "note": "back-to-back 32x32x16 bf16 MFMAs, nothing else on the CU, ~70-100 ms per run"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -128,6 +128,21 @@ int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const
                               int B, int N_max, int H, int d,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Diagnostic, not part of the method: the matrix-core ceiling of the machine, for the measurement the
+ * benchmark reports next to the attention kernels.  Launches 512 workgroups of 512 threads in which every
+ * wave issues `iters` x 32 independent 32x32x16 bf16 MFMAs on caller-supplied operands (constant
+ * operands reach the nominal rate; random ones expose the power-limited sustained rate).
+ *   operands : in,  device, sigmoid_attn_diag_mfma_operand_bytes() bytes of bf16 data, 16-byte aligned
+ *   sink     : out, device, sigmoid_attn_diag_mfma_sink_bytes() bytes (keeps the work alive; content unspecified)
+ * sigmoid_attn_diag_mfma_flops(iters) is the number of floating-point operations one launch performs.
+ * The caller times the launch (events on `stream`).
+ */
+size_t sigmoid_attn_diag_mfma_operand_bytes(void);
+size_t sigmoid_attn_diag_mfma_sink_bytes(void);
+double sigmoid_attn_diag_mfma_flops(int iters);
+int sigmoid_attn_diag_mfma(const void *operands, void *sink, int iters, void *stream);
+
 /* Scratch bytes sigmoid_attn_bwd needs for this shape (0 on invalid shapes). */
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d);
 
