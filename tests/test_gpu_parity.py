@@ -84,6 +84,60 @@ def test_padded_inputs_do_not_influence_valid_outputs():
         assert np.array_equal(x, y)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_nan_and_inf_in_padded_rows_are_never_read(d):
+    # Stronger than the contract (finite padding): padded streamed rows are never fetched (the loader
+    # re-reads the last valid row and zeroes it) and padded owner rows are replaced by zeros at load, so
+    # even NaN / Inf bit patterns in the padding leave every output bit unchanged.
+    lens = (333, 150, 0)
+    w = W.make(3, 333, 2, d, lens, seed=23)
+    a = Dev(w)
+    ref = [to_host(a.fwd())] + [to_host(t) for t in a.bwd()]
+    w2 = W.make(3, 333, 2, d, lens, seed=23)
+    bits = {"q": 0x7FC0, "k": 0x7F80, "v": 0xFF80, "d_o": 0xFFC1}      # NaN, +Inf, -Inf, another NaN
+    b = Dev(w2)
+    for nm, pat in bits.items():
+        raw = getattr(b, nm).view(torch.int16)
+        for z, n in enumerate(lens):
+            raw[z, n:] = pat - 65536 if pat >= 32768 else pat
+    torch.cuda.synchronize()
+    new = [to_host(b.fwd())] + [to_host(t) for t in b.bwd()]
+    for x, y in zip(ref, new):
+        assert np.all(np.isfinite(y))
+        assert np.array_equal(x, y)
+
+
+def test_more_sequences_than_the_ranked_mapping_holds():
+    # B > 256: the work mapping falls back to batch order; every output tile must still be produced once.
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 97, size=300)
+    lens[:3] = (96, 0, 1)
+    w = W.make(300, 96, 1, 64, lens, seed=24)
+    say("B=300", check_against_oracle(w, slices=[(z, 0) for z in (0, 1, 2, 57, 150, 299)]))
+    dev = Dev(w)
+    for t in [dev.fwd()] + list(dev.bwd()):
+        got = to_host(t)
+        for z in range(300):
+            assert np.all(got[z, int(lens[z]):] == 0.0) and np.all(np.isfinite(got[z]))
+
+
+def test_on_a_side_stream():
+    w = W.make(2, 200, 2, 64, (200, 131), seed=25)
+    q, k, v, g = (to_dev(x) for x in (w.q, w.k, w.v, w.d_o))
+    sl, b = torch.from_numpy(w.seqlens).cuda(), torch.from_numpy(w.bias).cuda()
+    ref_o = binding.sigmoid_attn_fwd(q, k, v, sl, b, w.scale)
+    ref_g = binding.sigmoid_attn_bwd(q, k, v, g, sl, b, w.scale)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        o = binding.sigmoid_attn_fwd(q, k, v, sl, b, w.scale, stream=side)
+        grads = binding.sigmoid_attn_bwd(q, k, v, g, sl, b, w.scale, stream=side)
+    side.synchronize()
+    assert torch.equal(o.view(torch.int16), ref_o.view(torch.int16))
+    for x, y in zip(grads, ref_g):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
 def test_padding_invariance_across_n_max():
     # the same sequence under a larger N_max and with another batch neighbour: identical valid rows
     w = W.make(1, 200, 2, 64, (200,), seed=31)
