@@ -18,9 +18,9 @@ import time
 import numpy as np
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense bf16 MFMA
-# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-# profiles/sigattn_kernels_long_d64_N8192_hbm_traffic.md (calibrated against a 1 GiB copy); only valid for
-# the workload and kernel it was measured on.
+# HBM bytes per launch of the dominant kernel, from FETCH_SIZE / WRITE_SIZE counter runs of this benchmark
+# (calibrated against a 1 GiB copy; the summary lies next to the other profiler summaries); only valid
+# for the workload and kernel it was measured on.
 MEASURED_TRAFFIC_BYTES = {("long", 0, "bwd_dkdv"): int(388.5 * 2 ** 20)}
 PAPER_CONTEXT = "paper: 515.6 TFLOPS fwd / 373.5 bwd on H100, d=128, N=16384, unpadded (another machine; context only)"
 
@@ -63,7 +63,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
-              "DESIGN.md says how the path would shard.", file=sys.stderr)
+              "The path shards over batch and heads without any exchange step.", file=sys.stderr)
         return 2
 
     import torch
