@@ -75,3 +75,18 @@ def test_wide_head_config():
     dev = Dev(w)
     say("wide lengths", w.seqlens.tolist())
     say("wide sampled", sampled_rows_check(w, dev, [(0, 0), (1, 15), (0, 9)], rows_per_slice=16))
+
+
+def test_very_long_single_sequence_sampled_rows():
+    # one sequence far beyond the benchmark lengths (625 streamed tiles, a ragged tail, 157 owner tiles):
+    # exercises the 64-bit slice offsets and the longest streamed loop
+    w = W.make(1, 40000, 2, 64, (39987,), seed=9)
+    dev = Dev(w)
+    say("N=40000 sampled", sampled_rows_check(w, dev, [(0, 0), (0, 1)], rows_per_slice=12))
+
+
+def test_many_heads_wide_rows_sampled():
+    # large row stride (H * d = 8192 elements): lane offsets inside a streamed tile stay 32-bit
+    w = W.make(2, 1500, 64, 128, (1500, 700), seed=10)
+    dev = Dev(w)
+    say("H=64 d=128 sampled", sampled_rows_check(w, dev, [(0, 0), (1, 63), (0, 31)], rows_per_slice=8))
