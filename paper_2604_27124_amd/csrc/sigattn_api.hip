@@ -42,7 +42,7 @@ int launch(const Params &p, hipStream_t stream) {
 
 extern "C" {
 
-int sigmoid_attn_version(void) { return 100; }
+int sigmoid_attn_version(void) { return 200; }
 
 const char *sigmoid_attn_strerror(int code) {
     switch (code) {
