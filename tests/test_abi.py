@@ -122,3 +122,30 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 8, 1, 64, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         B.sigmoid_attn_fwd(x, x, x, torch.zeros(1, dtype=torch.int32), torch.zeros(1), 0.125)
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is usable from C: the header compiles as C99 with warnings as errors, and a C
+    program linked against the library reaches the host-only entry points (no GPU call is made)."""
+    import subprocess
+    src = tmp_path / "use_abi.c"
+    src.write_text(
+        '#include "sigmoid_attn.h"\n'
+        '#include <stdio.h>\n'
+        '#include <string.h>\n'
+        'int main(void) {\n'
+        '    if (sigmoid_attn_version() < 100) return 1;\n'
+        '    if (strcmp(sigmoid_attn_strerror(0), "success") != 0) return 2;\n'
+        '    if (sigmoid_attn_bwd_workspace_bytes(4, 8192, 12, 64) != 0) return 3;\n'
+        '    /* null tensors: rejected on the host before any device work */\n'
+        '    if (sigmoid_attn_fwd(NULL, NULL, NULL, NULL, NULL, NULL, 0.125f, 1, 64, 1, 64, NULL) >= 0) return 4;\n'
+        '    puts("ok");\n'
+        '    return 0;\n'
+        '}\n')
+    exe = tmp_path / "use_abi"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH),
+                    "-Wl,-rpath," + libdir], check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert out.stdout.strip() == "ok"
