@@ -1,0 +1,54 @@
+"""Host-side behaviour of the benchmark and of the entry module that needs no GPU: the one-GPU rule,
+loud failure without a device (there is no CPU fallback), and the shape of the oracle-timed baseline."""
+import importlib.util
+import os
+import subprocess
+import sys
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def run(*args):
+    return subprocess.run([sys.executable, *args], cwd=ROOT, capture_output=True, text=True, timeout=300)
+
+
+def load_bench():
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = run("bench.py", "--gpus", "2")
+    assert r.returncode != 0 and r.stdout.strip() == ""
+    assert "ONE GPU" in r.stderr
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the behaviour on a machine without a GPU")
+def test_bench_and_grid_fail_loudly_without_a_gpu():
+    for cmd in (("bench.py",), ("-m", "paper_2604_27124_amd.grid")):
+        r = run(*cmd)
+        assert r.returncode != 0 and r.stdout.strip() == ""
+        assert "no CPU fallback" in r.stderr
+
+
+def test_cpu_baseline_fields_and_flop_accounting():
+    from paper_2604_27124_amd import workloads as W
+    bench = load_bench()
+    w = W.generate("tiny", 0)
+    b = bench.cpu_baseline(w, budget_s=5.0)
+    assert b["kind"] == "oracle" and b["unit"] == "TFLOPS" and b["cores"] >= 1 and b["value"] > 0
+    assert "tiny" in b["sample"] and "4 of 4" in b["sample"]            # B = 2, H = 2: every slice fits the budget
+    flops = 14 * w.d * w.H * sum(int(n) ** 2 for n in w.seqlens)
+    assert abs(b["value"] * 1e12 * b["seconds"] - flops) <= 1e-6 * flops
+
+
+def test_entry_module_exposes_build_and_smoke():
+    spec = importlib.util.spec_from_file_location("graft_entry", os.path.join(ROOT, "__graft_entry__.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert callable(mod.build) and callable(mod.smoke)
