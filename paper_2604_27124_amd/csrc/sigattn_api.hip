@@ -93,7 +93,9 @@ static int fwd_impl(const void *q, const void *k, const void *v, void *o,
         if (L_k > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
         return launch<FWD, 64, 1, 8, 64, 72, 72, 4, 4>(p, s);
     }
-    return launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(p, s);
+    // d = 128: K is only read row-wise (272-byte rows), V only through the transposing reads, which at that
+    // stride ran at a quarter of their rate; 288-byte rows with the split column layout are conflict-free.
+    return launch<FWD, 128, 1, 8, 64, 136, 144, 1, 4>(p, s);
 }
 
 static int bwd_impl(const void *q, const void *k, const void *v, const void *d_o,
@@ -136,12 +138,12 @@ static int bwd_impl(const void *q, const void *k, const void *v, const void *d_o
             Params pv = pk;
             pv.q = p.k; pv.k = p.q; pv.v = p.d_o; pv.d_o = nullptr;
             pv.out0 = static_cast<bf16_t *>(dv);
-            int e = launch<FWD, 128, 1, 8, 64, 136, 136, 1, 4>(pv, s);
+            int e = launch<FWD, 128, 1, 8, 64, 136, 144, 1, 4>(pv, s);
             if (e) return e;
             Params pd = pk;
             pd.q = p.k; pd.d_o = p.v; pd.k = p.q; pd.v = p.d_o;
             pd.out0 = static_cast<bf16_t *>(dk);
-            e = launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pd, s);
+            e = launch<DQ, 128, 1, 8, 64, 144, 136, 1, 4>(pd, s);
             if (e) return e;
         }
     }
@@ -152,7 +154,7 @@ static int bwd_impl(const void *q, const void *k, const void *v, const void *d_o
         pq.out0 = static_cast<bf16_t *>(dq);
         pq.out1 = nullptr;
         const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4>(pq, s)
-                                : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2>(pq, s);
+                                : launch<DQ, 128, 1, 8, 64, 144, 136, 1, 4>(pq, s);
         if (e) return e;
     }
     return SIGATTN_OK;
@@ -223,7 +225,7 @@ int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const
     p.db_seq = reinterpret_cast<int32_t *>(p.db_part + nwg);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int e = (d == 64) ? launch<DQ, 64, 1, 8, 64, 72, 72, 1, 4, true>(p, s)
-                            : launch<DQ, 128, 1, 8, 64, 136, 136, 1, 2, true>(p, s);
+                            : launch<DQ, 128, 1, 8, 64, 144, 136, 1, 2, true>(p, s);
     if (e) return e;
     hipLaunchKernelGGL(sigattn_db_reduce, dim3((unsigned)B), dim3(256), 0, s, p.db_part, p.db_seq, (int)nwg, dbias);
     return hipGetLastError() == hipSuccess ? SIGATTN_OK : SIGATTN_ERR_LAUNCH;

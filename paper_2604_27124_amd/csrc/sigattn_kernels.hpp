@@ -123,10 +123,42 @@ struct Cfg {
     static constexpr int SLOTS = NOPS * QB;        // one MFMA per slot
     // VALU work: units of two score elements (one packed bf16 register of the next B operand).
     static constexpr int UNITS = QB * 8;
+    // LDS placement of a streamed row t: element offset t * LD + lds_shift(t).  The transposing 8-byte reads
+    // of a half-wave touch four consecutive rows, 64 bytes each; they are conflict-free when the row stride
+    // is 64 or 192 bytes modulo the 256 bytes of the banks (mode 1), or -- at D = 128, with the 32 output
+    // rows of one MFMA taken as two groups of 16 columns that lie 128 bytes apart -- 32 bytes modulo 256
+    // (mode 2).  Under such a stride the 16-byte row-wise reads of 16 consecutive rows would collide, so every
+    // group of four (mode 1) or eight (mode 2) rows is shifted by a further 16 bytes.  Mode 0 is the plain
+    // padded layout (stride 16 bytes modulo 32), which is conflict-free for the row-wise reads only.
+    static constexpr int lds_mode(int LD) {
+        return (2 * LD) % 256 == 192 ? 1 : (((2 * LD) % 256 == 32 && D == 128) ? 2 : 0);
+    }
+    static constexpr int LM1 = lds_mode(LD1), LM2 = lds_mode(LD2);
+    static_assert(LM1 != 1 || LD1 >= D + 24, "mode 1 shifts a row by up to 48 bytes");
+    static_assert(LM2 != 1 || LD2 >= D + 24, "mode 1 shifts a row by up to 48 bytes");
+    static_assert(LM1 != 2 || LD1 >= D + 8, "mode 2 shifts a row by up to 16 bytes");
+    static_assert(LM2 != 2 || LD2 >= D + 8, "mode 2 shifts a row by up to 16 bytes");
     static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
     static_assert(D % 32 == 0 && BN % 64 == 0, "tile shape (an even number of 32-row blocks per tile)");
     static_assert(LD1 % 8 == 0 && LD2 % 8 == 0 && LD1 >= D && LD2 >= D, "LDS row stride");
     static_assert((NB * NOPS) % RING == 0 && RING >= 2 && RING <= NOPS, "operand ring does not close over a tile");
+};
+
+// Element offset added to row `row` of a streamed tile in LDS (see Cfg::lds_mode), the extra offset of the
+// second transposing read (eight rows further on), and the column layout of the transposed operand.
+template <int LM>
+__device__ __forceinline__ constexpr int lds_shift(int row) {
+    return LM == 1 ? 8 * ((row >> 2) & 3) : (LM == 2 ? 8 * ((row >> 3) & 1) : 0);
+}
+template <int LM>
+struct TrLayout {
+    static constexpr int HI_EXTRA = LM == 1 ? 16 : (LM == 2 ? 8 : 0);   // lds_shift(row + 8) - lds_shift(row), row % 8 < 4
+    static constexpr int GROUP_COLS = LM == 2 ? 64 : 16;                // column distance of the two 16-lane groups
+    static constexpr int MB_COLS = LM == 2 ? 16 : 32;                   // column step from one output block to the next
+    // head-dim column of accumulator registers 4 q4 .. 4 q4 + 3 of output block mb (without the 4 g of the lane)
+    static constexpr int out_col(int mb, int q4) {
+        return LM == 2 ? 16 * mb + 64 * (q4 >> 1) + 8 * (q4 & 1) : 32 * mb + 8 * q4;
+    }
 };
 
 // The VALU instructions of one step as a flat list.  Each unit (two score elements) runs through three
@@ -373,14 +405,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     // ---- streamed tile movement: HBM -> registers -> LDS ring slot
     const int ntiles = (ns + BN - 1) / BN;
     u32x4 st1[C::PER], st2[C::PER];
+    // Thread tid moves chunk tid % CH of rows tid / CH + it * RPI, it = 0 .. PER - 1: one lane constant,
+    // everything else is uniform (scalar registers) or a compile-time offset.
+    constexpr int RPI = C::THREADS / C::CH;        // rows per pass of the workgroup over a tile
+    static_assert(C::THREADS % C::CH == 0 && (C::PER == 1 || RPI % 16 == 0), "a pass must keep the LDS row shift");
+    const int r0 = tid / C::CH, col0 = (tid % C::CH) * 8;
+    const unsigned ld_off0 = (unsigned)r0 * (unsigned)row_stride + (unsigned)col0;
     auto load_tile = [&](int t) {   // branch-free: rows beyond the valid length read a clamped row, then become 0
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
-            const int cid = tid + it * C::THREADS;
-            const int r = t * BN + cid / C::CH;
-            const int col = (cid % C::CH) * 8;
+            const int r = t * BN + it * RPI + r0;
             const bool ok = r < ns;
-            const size_t off = slice_s + (size_t)(ok ? r : ns - 1) * row_stride + col;
+            const size_t off = slice_s + (size_t)(ok ? r : ns - 1) * row_stride + col0;
             const u32x4 a = *reinterpret_cast<const u32x4 *>(y1 + off);
             const u32x4 b = *reinterpret_cast<const u32x4 *>(y2 + off);
             const u32x4 z4 = {0u, 0u, 0u, 0u};
@@ -389,45 +425,41 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         }
     };
     // Tiles that lie wholly below the valid length need neither the clamp nor the zero fill: their
-    // addresses are a uniform base (scalar registers, advanced per tile) plus a lane constant.
-    unsigned ld_off[C::PER];
-#pragma unroll
-    for (int it = 0; it < C::PER; ++it) {
-        const int cid = tid + it * C::THREADS;
-        ld_off[it] = (unsigned)(cid / C::CH) * (unsigned)row_stride + (unsigned)(cid % C::CH) * 8u;
-    }
+    // addresses are a uniform base (scalar registers, advanced per tile and pass) plus the lane constant.
     auto load_full_tile = [&](int t) {
         const bf16_t *b1 = y1 + slice_s + (size_t)t * BN * row_stride;
         const bf16_t *b2 = y2 + slice_s + (size_t)t * BN * row_stride;
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
-            st1[it] = *reinterpret_cast<const u32x4 *>(b1 + ld_off[it]);
-            st2[it] = *reinterpret_cast<const u32x4 *>(b2 + ld_off[it]);
+            st1[it] = *reinterpret_cast<const u32x4 *>(b1 + (size_t)it * RPI * row_stride + ld_off0);
+            st2[it] = *reinterpret_cast<const u32x4 *>(b2 + (size_t)it * RPI * row_stride + ld_off0);
         }
     };
     auto load_next = [&](int t) {   // t * BN + BN <= ns exactly when t < ntiles - 1
         if (t < ntiles - 1) load_full_tile(t);
         else load_tile(t);
     };
+    bf16_t *const w1 = y1s + r0 * LD1 + lds_shift<C::LM1>(r0) + col0;   // LDS home of this thread's chunk, pass 0, slot 0
+    bf16_t *const w2 = y2s + r0 * LD2 + lds_shift<C::LM2>(r0) + col0;
     auto store_tile = [&](int slot) {
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
-            const int cid = tid + it * C::THREADS;
-            const int r = cid / C::CH;
-            const int col = (cid % C::CH) * 8;
-            *reinterpret_cast<u32x4 *>(y1s + (slot * BN + r) * LD1 + col) = st1[it];
-            *reinterpret_cast<u32x4 *>(y2s + (slot * BN + r) * LD2 + col) = st2[it];
+            *reinterpret_cast<u32x4 *>(w1 + (slot * BN + it * RPI) * LD1) = st1[it];
+            *reinterpret_cast<u32x4 *>(w2 + (slot * BN + it * RPI) * LD2) = st2[it];
         }
     };
 
     // lane-constant pieces of the LDS addresses
     const int i16 = lane & 15, g16 = (lane >> 4) & 1;
+    using TL1 = TrLayout<C::LM1>;
+    using TL2 = TrLayout<C::LM2>;
     const int tr_row = 4 * g + (i16 >> 2);         // transposed A operand: rows 4 g + 0..3 (and + 8)
-    const int tr_col = 16 * g16 + 4 * (i16 & 3);   // 16 output rows (head-dim columns) per 16-lane group
-    const bf16_t *rd1 = y1s + c * LD1 + 8 * g;     // row-wise A operand: row c, columns 16 ks + 8 g
-    const bf16_t *rd2 = y2s + c * LD2 + 8 * g;
-    const bf16_t *tr1 = y1s + tr_row * LD1 + tr_col;
-    const bf16_t *tr2 = y2s + tr_row * LD2 + tr_col;
+    // 16 output rows (head-dim columns) per 16-lane group; block and tile offsets are multiples of 16 rows and
+    // leave the shift of a row unchanged, so every address stays a lane constant plus an immediate
+    const bf16_t *rd1 = y1s + c * LD1 + lds_shift<C::LM1>(c) + 8 * g;     // row-wise A operand: row c, columns 16 ks + 8 g
+    const bf16_t *rd2 = y2s + c * LD2 + lds_shift<C::LM2>(c) + 8 * g;
+    const bf16_t *tr1 = y1s + tr_row * LD1 + lds_shift<C::LM1>(tr_row) + TL1::GROUP_COLS * g16 + 4 * (i16 & 3);
+    const bf16_t *tr2 = y2s + tr_row * LD2 + lds_shift<C::LM2>(tr_row) + TL2::GROUP_COLS * g16 + 4 * (i16 & 3);
 
     // Score accumulators and bf16 operands, double buffered by block parity.
     f32x16 sbuf[2][QB], dbuf[2][Q2];
@@ -458,11 +490,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             // FWD contracts V^T (tensor 2); DQ contracts K^T (tensor 1); DKDV: Q^T (1) for dK, dO^T (2) for dV
             constexpr bool second = (MODE == FWD) || (MODE == DKDV && which == 1);
             if constexpr (second) {
-                const bf16_t *a = tr2 + row * LD2 + 32 * mb;
-                return lds_read_tr(a, a + 8 * LD2);
+                const bf16_t *a = tr2 + row * LD2 + TL2::MB_COLS * mb;
+                return lds_read_tr(a, a + 8 * LD2 + TL2::HI_EXTRA);
             } else {
-                const bf16_t *a = tr1 + row * LD1 + 32 * mb;
-                return lds_read_tr(a, a + 8 * LD1);
+                const bf16_t *a = tr1 + row * LD1 + TL1::MB_COLS * mb;
+                return lds_read_tr(a, a + 8 * LD1 + TL1::HI_EXTRA);
             }
         }
     };
@@ -594,13 +626,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             for (int ks = 0; ks < C::KS; ++ks) xa[qb][ks] = scale_bf16x8(xa[qb][ks], c1);
 #pragma unroll
         for (int it = 0; it < C::PER; ++it) {
-            const int cid = tid + it * C::THREADS;
-            const int r = cid / C::CH;
-            const int col = (cid % C::CH) * 8;
-            *reinterpret_cast<u32x4 *>(y1s + r * LD1 + col) = a1[it];
-            *reinterpret_cast<u32x4 *>(y2s + r * LD2 + col) = a2[it];
-            *reinterpret_cast<u32x4 *>(y1s + (BN + r) * LD1 + col) = b1[it];
-            *reinterpret_cast<u32x4 *>(y2s + (BN + r) * LD2 + col) = b2[it];
+            *reinterpret_cast<u32x4 *>(w1 + (it * RPI) * LD1) = a1[it];
+            *reinterpret_cast<u32x4 *>(w2 + (it * RPI) * LD2) = a2[it];
+            *reinterpret_cast<u32x4 *>(w1 + (BN + it * RPI) * LD1) = b1[it];
+            *reinterpret_cast<u32x4 *>(w2 + (BN + it * RPI) * LD2) = b2[it];
         }
     }
     __syncthreads();
@@ -715,7 +744,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     }
 
     // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
-    // register i holds head-dim column 32 mb + 8 (i/4) + 4 g + (i%4): four consecutive columns per store.
+    // register i holds head-dim column out_col(mb, i/4) + 4 g + (i%4) of the layout its transposed operand
+    // was read with (plain: 32 mb + 8 (i/4)): four consecutive columns per store.
+    using TL_ACC0 = TrLayout<(MODE == FWD) ? C::LM2 : C::LM1>;      // FWD contracts V^T; DQ K^T; DKDV Q^T (acc0), dO^T (acc1)
+    using TL_ACC1 = TrLayout<C::LM2>;
     const float oscale = (MODE == FWD) ? 1.0f : p.scale;            // dQ and dK carry the factor `scale`
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -732,14 +764,14 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                     w0[0] = pack_bf16(acc0[qb][mb][4 * q4 + 0] * oscale, acc0[qb][mb][4 * q4 + 1] * oscale);
                     w0[1] = pack_bf16(acc0[qb][mb][4 * q4 + 2] * oscale, acc0[qb][mb][4 * q4 + 3] * oscale);
                 }
-                *reinterpret_cast<u32x2 *>(p.out0 + off + 32 * mb + 8 * q4) = w0;
+                *reinterpret_cast<u32x2 *>(p.out0 + off + TL_ACC0::out_col(mb, q4)) = w0;
                 if (MODE == DKDV) {
                     u32x2 w1 = {0u, 0u};
                     if (ok) {
                         w1[0] = pack_bf16(acc1[qb][mb][4 * q4 + 0], acc1[qb][mb][4 * q4 + 1]);
                         w1[1] = pack_bf16(acc1[qb][mb][4 * q4 + 2], acc1[qb][mb][4 * q4 + 3]);
                     }
-                    *reinterpret_cast<u32x2 *>(p.out1 + off + 32 * mb + 8 * q4) = w1;
+                    *reinterpret_cast<u32x2 *>(p.out1 + off + TL_ACC1::out_col(mb, q4)) = w1;
                 }
             }
         }
