@@ -743,35 +743,38 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         }
     }
 
-    // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane holds owner row c of each block,
-    // register i holds head-dim column out_col(mb, i/4) + 4 g + (i%4) of the layout its transposed operand
-    // was read with (plain: 32 mb + 8 (i/4)): four consecutive columns per store.
+    // ---- epilogue: transposed fp32 accumulators -> bf16 rows.  Lane (c, g) holds owner row c of each block;
+    // registers 4 q4 .. 4 q4 + 3 of output block mb hold head-dim columns out_col(mb, q4) + 4 g + 0..3 of the
+    // layout the transposed operand was read with (plain: 32 mb + 8 q4).  The two lanes of a row (32 apart)
+    // exchange halves -- lane g = 0 takes the even q4, lane g = 1 the odd ones -- so that each lane stores
+    // whole 16-byte chunks: a quarter of the store instructions and write requests of 8-byte stores.
     using TL_ACC0 = TrLayout<(MODE == FWD) ? C::LM2 : C::LM1>;      // FWD contracts V^T; DQ K^T; DKDV Q^T (acc0), dO^T (acc1)
     using TL_ACC1 = TrLayout<C::LM2>;
     const float oscale = (MODE == FWD) ? 1.0f : p.scale;            // dQ and dK carry the factor `scale`
+    auto chunk = [&](const f32x16 &a, const int pr, const float f) {   // columns of q4 = 2 pr + g
+        const unsigned e0 = pack_bf16(a[8 * pr + 0] * f, a[8 * pr + 1] * f), e1 = pack_bf16(a[8 * pr + 2] * f, a[8 * pr + 3] * f);
+        const unsigned o0 = pack_bf16(a[8 * pr + 4] * f, a[8 * pr + 5] * f), o1 = pack_bf16(a[8 * pr + 6] * f, a[8 * pr + 7] * f);
+        const auto s0 = __builtin_amdgcn_permlane32_swap(e0, o0, false, false);   // {lower half: e0 | o0 of g = 0, upper: of g = 1}
+        const auto s1 = __builtin_amdgcn_permlane32_swap(e1, o1, false, false);
+        const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
+        return w;
+    };
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const int r = wrow0 + 32 * qb + c;
-        if (r >= p.N) continue;
+        const bool inside = r < p.N;                                 // both lanes of a row agree on these two
         const bool ok = r < n;                                       // padded owner rows are written as zero
-        const size_t off = slice + (size_t)r * row_stride + 4 * g;
+        const size_t off = slice + (size_t)(inside ? r : 0) * row_stride + 8 * g;
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                u32x2 w0 = {0u, 0u};
-                if (ok) {
-                    w0[0] = pack_bf16(acc0[qb][mb][4 * q4 + 0] * oscale, acc0[qb][mb][4 * q4 + 1] * oscale);
-                    w0[1] = pack_bf16(acc0[qb][mb][4 * q4 + 2] * oscale, acc0[qb][mb][4 * q4 + 3] * oscale);
-                }
-                *reinterpret_cast<u32x2 *>(p.out0 + off + TL_ACC0::out_col(mb, q4)) = w0;
+            for (int pr = 0; pr < 2; ++pr) {
+                const u32x4 w0 = chunk(acc0[qb][mb], pr, oscale);
+                if (inside) *reinterpret_cast<u32x4 *>(p.out0 + off + TL_ACC0::out_col(mb, 2 * pr)) = ok ? w0 : z4;
                 if (MODE == DKDV) {
-                    u32x2 w1 = {0u, 0u};
-                    if (ok) {
-                        w1[0] = pack_bf16(acc1[qb][mb][4 * q4 + 0], acc1[qb][mb][4 * q4 + 1]);
-                        w1[1] = pack_bf16(acc1[qb][mb][4 * q4 + 2], acc1[qb][mb][4 * q4 + 3]);
-                    }
-                    *reinterpret_cast<u32x2 *>(p.out1 + off + TL_ACC1::out_col(mb, q4)) = w1;
+                    const u32x4 w1 = chunk(acc1[MODE == DKDV ? qb : 0][MODE == DKDV ? mb : 0], pr, 1.0f);
+                    if (inside) *reinterpret_cast<u32x4 *>(p.out1 + off + TL_ACC1::out_col(mb, 2 * pr)) = ok ? w1 : z4;
                 }
             }
         }
