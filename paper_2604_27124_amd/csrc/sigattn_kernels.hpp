@@ -213,52 +213,43 @@ constexpr int MAP_MAX_B = 256;
 template <int BM, int THREADS>
 __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n, int &m0) {
     __shared__ int s_len[MAP_MAX_B];      // clamped valid length, by batch index
-    __shared__ int s_seq[MAP_MAX_B];      // batch index, by rank (longest first)
     __shared__ int s_res[4];              // z, n, h, m0 of this workgroup
+    static_assert((BM & (BM - 1)) == 0, "owner tile rows: a power of two");
     const int T = (p.N + BM - 1) / BM;    // owner tiles per (z, h), padded ones included
     const int id = blockIdx.x;
     if (p.B <= MAP_MAX_B) {
-        // Ranked lists: valid tiles by rank (longest sequence first), then padded tiles by batch index.
-        // One thread per sequence sums the tile counts in front of its own (independent LDS reads, no
-        // dependent chain) and the one whose range holds this workgroup's id publishes the answer.
+        // Id ranges: the valid tiles of every sequence, longest sequence first (ties in batch order), H ids
+        // per tile; then the padded tiles in batch order.  One thread per sequence sums, in a single pass over
+        // the lengths (uniform LDS reads, no dependent chain), the tiles in front of its own ranges, and the
+        // thread whose range holds this workgroup's id publishes the answer.
         for (int t = threadIdx.x; t < p.B; t += THREADS) {
             const int v = p.seqlens[t];
             s_len[t] = v < 0 ? 0 : (v > p.N ? p.N : v);
         }
         __syncthreads();
         for (int t = threadIdx.x; t < p.B; t += THREADS) {
-            const int mine = s_len[t];
-            int rank = 0;
-            for (int u = 0; u < p.B; ++u) {
-                const int o = s_len[u];
-                rank += (o > mine || (o == mine && u < t)) ? 1 : 0;
-            }
-            s_seq[rank] = t;
-        }
-        __syncthreads();
-        for (int r = threadIdx.x; r < p.B; r += THREADS) {
+            const int mine = s_len[t], my_tiles = (mine + BM - 1) / BM;
             int before_valid = 0, before_padded = 0, all_valid = 0;
+#pragma unroll 8
             for (int u = 0; u < p.B; ++u) {
-                const int tiles_ranked = (s_len[s_seq[u]] + BM - 1) / BM;     // valid tiles of the sequence of rank u
-                const int tiles_batch = (s_len[u] + BM - 1) / BM;             // valid tiles of sequence u
-                all_valid += tiles_ranked;
-                before_valid += (u < r) ? tiles_ranked : 0;
-                before_padded += (u < r) ? (T - tiles_batch) : 0;
+                const int o = s_len[u], tiles = (o + BM - 1) / BM;
+                const bool ahead = o > mine || (o == mine && u < t);
+                before_valid += ahead ? tiles : 0;
+                before_padded += (u < t) ? (T - tiles) : 0;
+                all_valid += tiles;
             }
-            {   // valid tiles of the sequence of rank r
-                const int b = s_seq[r], len = s_len[b];
-                const int lo = before_valid * p.H, cnt = ((len + BM - 1) / BM) * p.H;
+            {   // valid tiles of sequence t
+                const int lo = before_valid * p.H, cnt = my_tiles * p.H;
                 if (id >= lo && id < lo + cnt) {
                     const int rest = id - lo;
-                    s_res[0] = b; s_res[1] = len; s_res[2] = rest % p.H; s_res[3] = (rest / p.H) * BM;
+                    s_res[0] = t; s_res[1] = mine; s_res[2] = rest % p.H; s_res[3] = (rest / p.H) * BM;
                 }
             }
-            {   // padded tiles of sequence r (batch order)
-                const int len = s_len[r], first = (len + BM - 1) / BM;
-                const int lo = (all_valid + before_padded) * p.H, cnt = (T - first) * p.H;
+            {   // padded tiles of sequence t
+                const int lo = (all_valid + before_padded) * p.H, cnt = (T - my_tiles) * p.H;
                 if (id >= lo && id < lo + cnt) {
                     const int rest = id - lo;
-                    s_res[0] = r; s_res[1] = len; s_res[2] = rest % p.H; s_res[3] = (first + rest / p.H) * BM;
+                    s_res[0] = t; s_res[1] = mine; s_res[2] = rest % p.H; s_res[3] = (my_tiles + rest / p.H) * BM;
                 }
             }
         }
