@@ -123,19 +123,16 @@ struct Cfg {
     static constexpr int SLOTS = NOPS * QB;        // one MFMA per slot
     // VALU work: units of two score elements (one packed bf16 register of the next B operand).
     static constexpr int UNITS = QB * 8;
-    // LDS placement of a streamed row t: element offset t * LD + lds_shift(t).  The transposing 8-byte reads
-    // of a half-wave touch four consecutive rows, 64 bytes each; they are conflict-free when the row stride
-    // is 64 or 192 bytes modulo the 256 bytes of the banks (mode 1), or -- at D = 128, with the 32 output
-    // rows of one MFMA taken as two groups of 16 columns that lie 128 bytes apart -- 32 bytes modulo 256
-    // (mode 2).  Under such a stride the 16-byte row-wise reads of 16 consecutive rows would collide, so every
-    // group of four (mode 1) or eight (mode 2) rows is shifted by a further 16 bytes.  Mode 0 is the plain
-    // padded layout (stride 16 bytes modulo 32), which is conflict-free for the row-wise reads only.
-    static constexpr int lds_mode(int LD) {
-        return (2 * LD) % 256 == 192 ? 1 : (((2 * LD) % 256 == 32 && D == 128) ? 2 : 0);
-    }
+    // LDS placement of a streamed row t: element offset t * LD + lds_shift(t).  Mode 0 is the plain padded
+    // layout (row stride 16 bytes modulo 32): conflict-free for the 16-byte row-wise reads of 16 consecutive
+    // rows.  The transposing 8-byte reads of a half-wave touch four consecutive rows; at D = 64 that layout
+    // costs them nothing measurable, at D = 128 (272-byte rows) it quarters their rate.  Mode 2, for D = 128
+    // tensors that are read transposed: 288-byte rows (32 bytes modulo the 256 bytes of the banks), the 32
+    // output rows of one MFMA taken as two groups of 16 head-dim columns that lie 128 bytes apart, so that
+    // the four rows of a read fall into disjoint banks; every second group of eight rows is shifted by a
+    // further 16 bytes, which keeps the row-wise reads conflict-free under that stride.
+    static constexpr int lds_mode(int LD) { return ((2 * LD) % 256 == 32 && D == 128) ? 2 : 0; }
     static constexpr int LM1 = lds_mode(LD1), LM2 = lds_mode(LD2);
-    static_assert(LM1 != 1 || LD1 >= D + 24, "mode 1 shifts a row by up to 48 bytes");
-    static_assert(LM2 != 1 || LD2 >= D + 24, "mode 1 shifts a row by up to 48 bytes");
     static_assert(LM1 != 2 || LD1 >= D + 8, "mode 2 shifts a row by up to 16 bytes");
     static_assert(LM2 != 2 || LD2 >= D + 8, "mode 2 shifts a row by up to 16 bytes");
     static_assert((BN * CH) % THREADS == 0, "tile does not split evenly over the workgroup");
@@ -148,11 +145,11 @@ struct Cfg {
 // second transposing read (eight rows further on), and the column layout of the transposed operand.
 template <int LM>
 __device__ __forceinline__ constexpr int lds_shift(int row) {
-    return LM == 1 ? 8 * ((row >> 2) & 3) : (LM == 2 ? 8 * ((row >> 3) & 1) : 0);
+    return LM == 2 ? 8 * ((row >> 3) & 1) : 0;
 }
 template <int LM>
 struct TrLayout {
-    static constexpr int HI_EXTRA = LM == 1 ? 16 : (LM == 2 ? 8 : 0);   // lds_shift(row + 8) - lds_shift(row), row % 8 < 4
+    static constexpr int HI_EXTRA = LM == 2 ? 8 : 0;                    // lds_shift(row + 8) - lds_shift(row), row % 8 < 4
     static constexpr int GROUP_COLS = LM == 2 ? 64 : 16;                // column distance of the two 16-lane groups
     static constexpr int MB_COLS = LM == 2 ? 16 : 32;                   // column step from one output block to the next
     // head-dim column of accumulator registers 4 q4 .. 4 q4 + 3 of output block mb (without the 4 g of the lane)
