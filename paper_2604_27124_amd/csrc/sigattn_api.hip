@@ -88,9 +88,10 @@ static int fwd_impl(const void *q, const void *k, const void *v, void *o,
     if (d == 64) {
         // 512-row owner tiles (two owner blocks per wave) feed two MFMAs from every LDS operand read and win
         // on long sequences; 256-row tiles need half the registers, so two workgroups share a CU, and they
-        // halve the granularity of the grid: measured better up to 4096 streamed rows (the host sees the
-        // padded lengths only).
-        if (L_k > 4096) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
+        // halve the granularity of the grid: measured better up to 4096 streamed rows unless the grid of
+        // 512-row tiles still fills the chip four times over (the host sees the padded lengths only).
+        const long long wgs512 = (long long)B * H * ((L_q + 511) / 512);
+        if (L_k > 4096 || (L_k >= 2048 && wgs512 >= 1024)) return launch<FWD, 64, 2, 8, 64, 72, 72, 1, 4>(p, s);
         return launch<FWD, 64, 1, 8, 64, 72, 72, 4, 4>(p, s);
     }
     // d = 128: K is only read row-wise (272-byte rows), V only through the transposing reads, which at that
