@@ -47,6 +47,19 @@ def test_several_tiles_ragged_tail_d128():
     say("ragged d128", check_against_oracle(w))
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes(seed):
+    # shapes, lengths and head counts drawn at random (seeded): tile edges, owner blocks and the work
+    # mapping are hit in combinations the hand-picked cases do not list
+    rng = np.random.default_rng(1000 + seed)
+    d = 64 if seed % 3 else 128
+    B, H = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+    N = int(rng.integers(1, 641))
+    seqlens = tuple(int(x) for x in rng.integers(0, N + 1, size=B))
+    w = W.make(B, N, H, d, seqlens, seed=seed, qkv_std=float(rng.uniform(0.5, 2.0)))
+    say("random shape", dict(B=B, N=N, H=H, d=d, seqlens=seqlens), check_against_oracle(w))
+
+
 def test_large_logits_saturate_without_nan():
     w = W.make(1, 256, 2, 64, (200,), seed=13, qkv_std=4.0)      # |scale * s| up to ~ 60
     say("large logits", check_against_oracle(w))
