@@ -129,6 +129,17 @@ int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same with separate query and key lengths (layouts and lengths as for sigmoid_attn_cross_bwd):
+ * db_z sums dS_ij over heads, i < n_q and j < n_k.  The workspace is sized by the query side,
+ * nwg = B * H * ceil(L_q / 256).
+ */
+size_t sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(int B, int L_q, int L_k, int H, int d);
+int sigmoid_attn_cross_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq,
+                                    float *dbias, const int32_t *seqlens_q, const int32_t *seqlens_k,
+                                    const float *bias, float scale, int B, int L_q, int L_k, int H, int d,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Diagnostic, not part of the method: the matrix-core ceiling of the machine, for the measurement the
  * benchmark reports next to the attention kernels.  Launches 512 workgroups of 512 threads in which every
  * wave issues `iters` x 32 independent 32x32x16 bf16 MFMAs on caller-supplied operands (constant

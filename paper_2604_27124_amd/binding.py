@@ -25,6 +25,7 @@ EXPORTS = ("sigmoid_attn_version", "sigmoid_attn_strerror", "sigmoid_attn_fwd", 
            "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes",
            "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd",
            "sigmoid_attn_bwd_dq_dbias", "sigmoid_attn_bwd_dq_dbias_workspace_bytes",
+           "sigmoid_attn_cross_bwd_dq_dbias", "sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes",
            "sigmoid_attn_diag_mfma", "sigmoid_attn_diag_mfma_operand_bytes", "sigmoid_attn_diag_mfma_sink_bytes",
            "sigmoid_attn_diag_mfma_flops")
 
@@ -66,6 +67,10 @@ def load() -> ctypes.CDLL:
         lib.sigmoid_attn_bwd_dq_dbias.restype = ci
         lib.sigmoid_attn_bwd_dq_dbias_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.sigmoid_attn_bwd_dq_dbias_workspace_bytes.restype = sz
+        lib.sigmoid_attn_cross_bwd_dq_dbias.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, ci, vp, sz, vp]
+        lib.sigmoid_attn_cross_bwd_dq_dbias.restype = ci
+        lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.restype = sz
         lib.sigmoid_attn_diag_mfma.argtypes = [vp, vp, ci, vp]
         lib.sigmoid_attn_diag_mfma.restype = ci
         lib.sigmoid_attn_diag_mfma_operand_bytes.argtypes = []
@@ -276,6 +281,38 @@ def sigmoid_attn_bwd_dq_dbias(q, k, v, d_o, seqlens, bias, scale: float, dq=None
                                           dbias.data_ptr(), seqlens.data_ptr(), bias.data_ptr(), float(scale),
                                           B, N, H, d, workspace.data_ptr(),
                                           workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SIGATTN_OK:
+        raise SigAttnError(rc)
+    return dq, dbias
+
+
+def sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(B: int, L_q: int, L_k: int, H: int, d: int) -> int:
+    return int(load().sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(B, L_q, L_k, H, d))
+
+
+def sigmoid_attn_cross_bwd_dq_dbias(q, k, v, d_o, seqlens_q, seqlens_k, bias, scale: float, dq=None, dbias=None,
+                                    workspace=None, stream=None):
+    """(dQ, dbias [B] float32) with separate query and key lengths."""
+    import torch
+    _check_cross(q, k, v)
+    B, L_q, H, d = q.shape
+    L_k = k.shape[1]
+    _check(d_o, "d_o", q.shape)
+    _check_vec(seqlens_q, "seqlens_q", B, torch.int32)
+    _check_vec(seqlens_k, "seqlens_k", B, torch.int32)
+    _check_vec(bias, "bias", B, torch.float32)
+    dq = torch.empty_like(q) if dq is None else dq
+    _check(dq, "dq", q.shape)
+    dbias = torch.empty(B, dtype=torch.float32, device=q.device) if dbias is None else dbias
+    _check_vec(dbias, "dbias", B, torch.float32)
+    need = sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(B, L_q, L_k, H, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    rc = load().sigmoid_attn_cross_bwd_dq_dbias(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+                                                dq.data_ptr(), dbias.data_ptr(), seqlens_q.data_ptr(),
+                                                seqlens_k.data_ptr(), bias.data_ptr(), float(scale), B, L_q, L_k, H, d,
+                                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                _stream_ptr(stream))
     if rc != SIGATTN_OK:
         raise SigAttnError(rc)
     return dq, dbias

@@ -42,7 +42,7 @@ int launch(const Params &p, hipStream_t stream) {
 
 extern "C" {
 
-int sigmoid_attn_version(void) { return 200; }
+int sigmoid_attn_version(void) { return 300; }
 
 const char *sigmoid_attn_strerror(int code) {
     switch (code) {
@@ -200,28 +200,36 @@ size_t sigmoid_attn_bwd_dq_dbias_workspace_bytes(int B, int N_max, int H, int d)
     return (size_t)dq_workgroups(B, N_max, H) * (sizeof(float) + sizeof(int32_t));
 }
 
-int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq, float *dbias,
-                              const int32_t *seqlens, const float *bias, float scale,
-                              int B, int N_max, int H, int d,
-                              void *workspace, size_t workspace_bytes, void *stream) {
-    if (!q || !k || !v || !d_o || !dq || !dbias || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
-    if (int e = check_shape(B, N_max, H, d)) return e;
+size_t sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(int B, int L_q, int L_k, int H, int d) {
+    if (check_shape(B, L_k, H, d) != SIGATTN_OK) return 0;
+    return sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, L_q, H, d);     // one partial per 256-row query tile
+}
+
+static int dq_dbias_impl(const void *q, const void *k, const void *v, const void *d_o, void *dq, float *dbias,
+                         const int32_t *seqlens_q, const int32_t *seqlens_k, const float *bias, float scale,
+                         int B, int L_q, int L_k, int H, int d,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    if (!q || !k || !v || !d_o || !dq || !dbias || !seqlens_q || !seqlens_k || !bias || !std::isfinite(scale))
+        return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, L_q, H, d)) return e;
+    if (int e = check_shape(B, L_k, H, d)) return e;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq)) return SIGATTN_ERR_MISALIGNED;
-    const size_t need = sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, N_max, H, d);
+    const size_t need = sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, L_q, H, d);
     if (!workspace || workspace_bytes < need) return SIGATTN_ERR_WORKSPACE;
     if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(dbias) & 3u)) return SIGATTN_ERR_MISALIGNED;
 
-    const long long nwg = dq_workgroups(B, N_max, H);
+    const long long nwg = dq_workgroups(B, L_q, H);
     Params p{};
     p.q = static_cast<const bf16_t *>(q);
     p.k = static_cast<const bf16_t *>(k);
     p.v = static_cast<const bf16_t *>(v);
     p.d_o = static_cast<const bf16_t *>(d_o);
     p.out0 = static_cast<bf16_t *>(dq);
-    p.seqlens = seqlens; p.seqlens_str = seqlens;
+    p.seqlens = seqlens_q;          // owner side: queries
+    p.seqlens_str = seqlens_k;      // streamed side: keys / values
     p.bias = bias;
     p.scale = scale;
-    p.B = B; p.N = N_max; p.N_str = N_max; p.H = H;
+    p.B = B; p.N = L_q; p.N_str = L_k; p.H = H;
     p.db_part = static_cast<float *>(workspace);
     p.db_seq = reinterpret_cast<int32_t *>(p.db_part + nwg);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -230,6 +238,22 @@ int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const
     if (e) return e;
     hipLaunchKernelGGL(sigattn_db_reduce, dim3((unsigned)B), dim3(256), 0, s, p.db_part, p.db_seq, (int)nwg, dbias);
     return hipGetLastError() == hipSuccess ? SIGATTN_OK : SIGATTN_ERR_LAUNCH;
+}
+
+int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq, float *dbias,
+                              const int32_t *seqlens, const float *bias, float scale,
+                              int B, int N_max, int H, int d,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    return dq_dbias_impl(q, k, v, d_o, dq, dbias, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d,
+                         workspace, workspace_bytes, stream);
+}
+
+int sigmoid_attn_cross_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq,
+                                    float *dbias, const int32_t *seqlens_q, const int32_t *seqlens_k,
+                                    const float *bias, float scale, int B, int L_q, int L_k, int H, int d,
+                                    void *workspace, size_t workspace_bytes, void *stream) {
+    return dq_dbias_impl(q, k, v, d_o, dq, dbias, seqlens_q, seqlens_k, bias, scale, B, L_q, L_k, H, d,
+                         workspace, workspace_bytes, stream);
 }
 
 int sigmoid_attn_cross_fwd(const void *q, const void *k, const void *v, void *o,

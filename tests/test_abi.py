@@ -117,6 +117,22 @@ def test_dq_dbias_argument_validation(lib):
     assert f(db=p + 2) == B.SIGATTN_ERR_MISALIGNED
 
 
+def test_cross_dq_dbias_argument_validation(lib):
+    ok = ctypes.c_void_p(256)
+    f = lib.sigmoid_attn_cross_bwd_dq_dbias
+    args = lambda **kw: [kw.get(n, ok) for n in ("q", "k", "v", "d_o", "dq", "dbias", "sq", "sk", "bias")] + \
+        [ctypes.c_float(kw.get("scale", 0.125)), kw.get("B", 2), kw.get("Lq", 300), kw.get("Lk", 520), kw.get("H", 2),
+         kw.get("d", 64), kw.get("ws", ok), ctypes.c_size_t(kw.get("wsb", 1 << 20)), None]
+    assert f(*args(sk=None)) == -1                       # a null pointer
+    assert f(*args(Lk=0)) == -1                          # a non-positive size
+    assert f(*args(d=96)) == -2                          # unsupported head dimension
+    assert f(*args(k=ctypes.c_void_p(8))) == -3          # misaligned tensor
+    assert f(*args(wsb=8)) == -4                         # workspace too small
+    need = lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(2, 300, 520, 2, 64)
+    assert need == 2 * 2 * 2 * 8 == lib.sigmoid_attn_bwd_dq_dbias_workspace_bytes(2, 300, 2, 64)
+    assert lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes(2, 300, 0, 2, 64) == 0
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 8, 1, 64, dtype=torch.bfloat16)

@@ -58,3 +58,28 @@ def test_dbias_on_the_tiny_workload():
     got, ref = run(w)
     scale = np.abs(ref).max()
     assert np.all(np.abs(got - ref) <= BWD_TOL * scale + 1e-3)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_cross_dbias_with_separate_lengths(d):
+    # queries and keys of different padded and valid lengths; V, dO >= 0 so that db does not cancel
+    B, Lq, Lk, H = 3, 300, 520, 2
+    rng = np.random.default_rng(40 + d)
+    mk = lambda L: W.round_to_bf16(rng.standard_normal((B, L, H, d)).astype(np.float32))
+    q, k, v, g = mk(Lq), mk(Lk), np.abs(mk(Lk)), np.abs(mk(Lq))
+    nq, nk = np.array([300, 41, 0], np.int32), np.array([77, 520, 300], np.int32)
+    bias = np.array([-4.0, -6.0, -5.0], np.float32)
+    scale = 1.0 / np.sqrt(d)
+    tq, tk, tv, tg = to_dev(q), to_dev(k), to_dev(v), to_dev(g)
+    sq, sk, tb = torch.from_numpy(nq).cuda(), torch.from_numpy(nk).cuda(), torch.from_numpy(bias).cuda()
+    dq, db = binding.sigmoid_attn_cross_bwd_dq_dbias(tq, tk, tv, tg, sq, sk, tb, scale,
+                                                     dq=torch.full_like(tq, float("nan")),
+                                                     dbias=torch.full((B,), float("nan"), device="cuda"))
+    dq_ref, _, _ = binding.sigmoid_attn_cross_bwd(tq, tk, tv, tg, sq, sk, tb, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(dq.view(torch.int16), dq_ref.view(torch.int16))      # same dQ as the plain cross kernel
+    _, _, _, ref = oracle.cross_bwd(q, k, v, g, nq, nk, bias, scale)
+    got = db.cpu().numpy().astype(np.float64)
+    print("cross dbias", d, got, ref, flush=True)
+    assert got[2] == 0.0 and ref[2] == 0.0                                  # no valid queries
+    assert np.all(np.abs(got[:2] - ref[:2]) <= BWD_TOL * np.abs(ref[:2]))
