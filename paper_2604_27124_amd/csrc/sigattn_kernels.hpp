@@ -202,8 +202,9 @@ __device__ __forceinline__ bf16x8 scale_bf16x8(const bf16x8 v, const float f) {
 // Longest-first work mapping.  The launch is a 1-D grid with one workgroup per owner tile of every
 // (z, h); hardware hands consecutive workgroup ids to the 8 XCDs round-robin and to free CUs in order.
 // Ids are therefore mapped so that the tiles of the LONGEST sequences come first (their cost is
-// proportional to the sequence's valid length) and every XCD receives every 8th tile of that sorted list;
-// wholly padded tiles, which only write zeros, come last.  Sequences are ranked inside the kernel from
+// proportional to the sequence's valid length), every XCD receives every 8th id of that sorted list, and
+// within one sequence the ids of one XCD are consecutive tiles of the same head; wholly padded tiles,
+// which only write zeros, come last.  Sequences are ranked inside the kernel from
 // seqlens (B <= MAP_MAX_B; larger batches keep batch order), so the host never needs the lengths.
 constexpr int MAP_MAX_B = 256;
 
@@ -235,11 +236,19 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
                 before_padded += (u < t) ? (T - tiles) : 0;
                 all_valid += tiles;
             }
-            {   // valid tiles of sequence t
+            {   // valid tiles of sequence t: ids lo .. lo + cnt - 1.  Hardware deals consecutive ids round-robin to
+                // the 8 XCDs, each with an L2 of its own; the ids that land on one XCD take consecutive tiles of
+                // one head (then of the next), so a head's streamed slab is fetched by one or two XCDs only.
                 const int lo = before_valid * p.H, cnt = my_tiles * p.H;
                 if (id >= lo && id < lo + cnt) {
-                    const int rest = id - lo;
-                    s_res[0] = t; s_res[1] = mine; s_res[2] = rest % p.H; s_res[3] = (rest / p.H) * BM;
+                    const int idx = id - lo, x = id & 7;
+                    int e = 0;                                      // ids of this range on XCDs below x
+                    for (int y = 0; y < x; ++y) {
+                        const int first = (y - lo) & 7;             // first index of the range that lands on XCD y
+                        e += (first < cnt) ? ((cnt - first + 7) >> 3) : 0;
+                    }
+                    e += (idx - ((x - lo) & 7)) >> 3;               // position among the ids on XCD x
+                    s_res[0] = t; s_res[1] = mine; s_res[2] = e / my_tiles; s_res[3] = (e % my_tiles) * BM;
                 }
             }
             {   // padded tiles of sequence t
