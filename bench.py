@@ -139,8 +139,9 @@ def main() -> int:
     if not args.no_mfma_ceiling:
         # the matrix cores alone, same process, same box: nominal rate on constant operands, power-limited
         # sustained rate on random ones (the latter is what any bf16 contraction on real data lives under)
-        rnd = binding.sigmoid_attn_diag_mfma_tflops("random")
-        cst = binding.sigmoid_attn_diag_mfma_tflops("constant")
+        from paper_2604_27124_amd import mfma_probe
+        rnd = mfma_probe.tflops("random")
+        cst = mfma_probe.tflops("constant")
         out["mfma_ceiling"] = {"random_operands_tflops": round(rnd, 1), "constant_operands_tflops": round(cst, 1),
                                "value_over_random_ceiling": round(tflops / rnd, 4),
                                "note": "back-to-back 32x32x16 bf16 MFMAs, nothing else on the CU, ~70-100 ms per run"}

@@ -16,7 +16,9 @@
  *     dP_ij = <dO_i, V_j>,   dS_ij = P_ij (1 - P_ij) dP_ij
  *     dV_j = sum_i P_ij dO_i,   dK_j = scale * sum_i dS_ij Q_i,   dQ_i = scale * sum_j dS_ij K_j
  *
- * over valid i, j only; padded rows of dQ, dK, dV are written as zero.
+ * over valid i, j only; padded rows of dQ, dK, dV are written as zero.  1 - P is formed without
+ * cancellation (as exp(-x) P), so dS keeps its relative accuracy on both saturated tails of sigma,
+ * for every score and bias whose exponentials fp32 can hold (|bias| up to about 80).
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -72,9 +74,9 @@ int sigmoid_attn_fwd(const void *q, const void *k, const void *v, void *o,
  * Backward pass (Alg. 2: dQ; Alg. 3: dK, dV).  Needs only the forward inputs and dO.
  *   q, k, v, d_o : in,  device bf16 [B, N_max, H, d]  (rows >= seqlens[z] of d_o are ignored)
  *   dq, dk, dv   : out, device bf16 [B, N_max, H, d]; padded rows are written as 0
- *   workspace    : device scratch of at least sigmoid_attn_bwd_workspace_bytes(...) bytes, 256-byte
- *                  aligned, owned by the caller, contents irrelevant on entry and undefined on exit;
- *                  may be NULL when that size is 0.
+ *   workspace    : device scratch of at least sigmoid_attn_bwd_workspace_bytes(...) bytes, owned by
+ *                  the caller, contents irrelevant on entry and undefined on exit.  That size is 0 for
+ *                  every shape (each kernel owns its output tiles), so NULL / 0 is accepted.
  */
 int sigmoid_attn_bwd(const void *q, const void *k, const void *v, const void *d_o,
                      void *dq, void *dk, void *dv,
@@ -138,21 +140,6 @@ int sigmoid_attn_cross_bwd_dq_dbias(const void *q, const void *k, const void *v,
                                     float *dbias, const int32_t *seqlens_q, const int32_t *seqlens_k,
                                     const float *bias, float scale, int B, int L_q, int L_k, int H, int d,
                                     void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Diagnostic, not part of the method: the matrix-core ceiling of the machine, for the measurement the
- * benchmark reports next to the attention kernels.  Launches 512 workgroups of 512 threads in which every
- * wave issues `iters` x 32 independent 32x32x16 bf16 MFMAs on caller-supplied operands (constant
- * operands reach the nominal rate; random ones expose the power-limited sustained rate).
- *   operands : in,  device, sigmoid_attn_diag_mfma_operand_bytes() bytes of bf16 data, 16-byte aligned
- *   sink     : out, device, sigmoid_attn_diag_mfma_sink_bytes() bytes (keeps the work alive; content unspecified)
- * sigmoid_attn_diag_mfma_flops(iters) is the number of floating-point operations one launch performs.
- * The caller times the launch (events on `stream`).
- */
-size_t sigmoid_attn_diag_mfma_operand_bytes(void);
-size_t sigmoid_attn_diag_mfma_sink_bytes(void);
-double sigmoid_attn_diag_mfma_flops(int iters);
-int sigmoid_attn_diag_mfma(const void *operands, void *sink, int iters, void *stream);
 
 /* Scratch bytes sigmoid_attn_bwd needs for this shape (0 on invalid shapes). */
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d);

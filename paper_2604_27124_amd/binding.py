@@ -25,9 +25,7 @@ EXPORTS = ("sigmoid_attn_version", "sigmoid_attn_strerror", "sigmoid_attn_fwd", 
            "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes",
            "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd",
            "sigmoid_attn_bwd_dq_dbias", "sigmoid_attn_bwd_dq_dbias_workspace_bytes",
-           "sigmoid_attn_cross_bwd_dq_dbias", "sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes",
-           "sigmoid_attn_diag_mfma", "sigmoid_attn_diag_mfma_operand_bytes", "sigmoid_attn_diag_mfma_sink_bytes",
-           "sigmoid_attn_diag_mfma_flops")
+           "sigmoid_attn_cross_bwd_dq_dbias", "sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes")
 
 _lib = None
 
@@ -71,14 +69,6 @@ def load() -> ctypes.CDLL:
         lib.sigmoid_attn_cross_bwd_dq_dbias.restype = ci
         lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.restype = sz
-        lib.sigmoid_attn_diag_mfma.argtypes = [vp, vp, ci, vp]
-        lib.sigmoid_attn_diag_mfma.restype = ci
-        lib.sigmoid_attn_diag_mfma_operand_bytes.argtypes = []
-        lib.sigmoid_attn_diag_mfma_operand_bytes.restype = sz
-        lib.sigmoid_attn_diag_mfma_sink_bytes.argtypes = []
-        lib.sigmoid_attn_diag_mfma_sink_bytes.restype = sz
-        lib.sigmoid_attn_diag_mfma_flops.argtypes = [ci]
-        lib.sigmoid_attn_diag_mfma_flops.restype = ctypes.c_double
         lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
         _lib = lib
@@ -316,32 +306,3 @@ def sigmoid_attn_cross_bwd_dq_dbias(q, k, v, d_o, seqlens_q, seqlens_k, bias, sc
     if rc != SIGATTN_OK:
         raise SigAttnError(rc)
     return dq, dbias
-
-
-def sigmoid_attn_diag_mfma_tflops(kind: str = "random", iters: int = 20000, repeats: int = 3, stream=None) -> float:
-    """Sustained rate (TFLOPS) of back-to-back bf16 MFMAs on `kind` operands ("random" N(0,1) or "constant"):
-    the machine's matrix-core ceiling under this kind of data, measured with events on the launch stream."""
-    import torch
-    lib = load()
-    n = lib.sigmoid_attn_diag_mfma_operand_bytes() // 2
-    if kind == "random":
-        g = torch.Generator(device="cuda"); g.manual_seed(0)
-        ops = torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)
-    elif kind == "constant":
-        ops = torch.ones(n, device="cuda", dtype=torch.bfloat16)
-    else:
-        raise ValueError("kind must be 'random' or 'constant'")
-    sink = torch.empty(lib.sigmoid_attn_diag_mfma_sink_bytes() // 4, device="cuda", dtype=torch.float32)
-    s = torch.cuda.current_stream() if stream is None else stream
-    best = 0.0
-    for _ in range(repeats):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(s)
-        rc = lib.sigmoid_attn_diag_mfma(ops.data_ptr(), sink.data_ptr(), int(iters), int(s.cuda_stream))
-        if rc != SIGATTN_OK:
-            raise SigAttnError(rc)
-        e1.record(s)
-        e1.synchronize()
-        last = lib.sigmoid_attn_diag_mfma_flops(int(iters)) / (e0.elapsed_time(e1) * 1e-3) / 1e12
-        best = last          # the last repeat: clocks have settled under the load
-    return best

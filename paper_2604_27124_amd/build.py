@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsigattn.so")
-SOURCES = ["sigattn_api.hip", "sigattn_diag.hip"]
+SOURCES = ["sigattn_api.hip"]
+PROBE_LIB = os.path.join(HERE, "libmfma_probe.so")      # measurement aid for the benchmark, a library of its own
+PROBE_SOURCES = ["mfma_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -25,17 +27,23 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False) -> str:
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIB,
-           *[os.path.join(CSRC, s) for s in SOURCES]]
+def _compile(lib: str, sources, verbose: bool) -> str:
+    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", lib,
+           *[os.path.join(CSRC, s) for s in sources]]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libsigattn.so")
-    return LIB
+        raise RuntimeError(f"hipcc failed building {os.path.basename(lib)}")
+    return lib
+
+
+def build_library(verbose: bool = False) -> str:
+    """libsigattn.so (the method) and libmfma_probe.so (the benchmark's matrix-core probe)."""
+    _compile(PROBE_LIB, PROBE_SOURCES, verbose)
+    return _compile(LIB, SOURCES, verbose)
 
 
 if __name__ == "__main__":

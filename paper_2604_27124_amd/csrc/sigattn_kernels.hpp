@@ -37,6 +37,7 @@ typedef __bf16 bf16_t;
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -92,6 +93,13 @@ __device__ __forceinline__ bf16x8 lds_read_tr(const bf16_t *p_lo, const bf16_t *
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SIGATTN_LDS_PTR(s16x4, p_hi));
     s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
+}
+
+// a * b under the rule 0 * x = 0 for every x, also +-inf and NaN (v_mul_legacy_f32).
+__device__ __forceinline__ float mul_zero_wins(float a, float b) {
+    float r;
+    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
@@ -386,15 +394,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             }
         }
 
-    // Bias gradient db = sum of dS over all valid pairs: one more MFMA per 16 streamed rows with an all-ones
-    // A operand puts the column sums of dS^T (the bf16 values that also feed dQ) into every row of accdb.
-    f32x16 accdb[WITH_DB ? QB : 1];
+    // Bias gradient db = sum of dS over all valid pairs: one more (small) MFMA per 16 streamed rows with an
+    // all-ones A operand sums the bf16 values that also feed dQ.  v_mfma_f32_16x16x32_bf16 reads the B operand
+    // of the 32-wide shape as 16 columns x 32 contraction slots: column j of its result is the sum over the
+    // lanes congruent to j modulo 16 -- which owner rows and streamed rows get mixed does not matter for a
+    // total -- and every row of the result holds the same 16 sums.
+    f32x4 accdb[WITH_DB ? QB : 1];
     bf16x8 ones;
     if (WITH_DB) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) accdb[qb][i] = 0.f;
+            for (int i = 0; i < 4; ++i) accdb[qb][i] = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) ones[i] = (bf16_t)1.0f;
     }
@@ -499,8 +510,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     // VALU work of one step: see ValuOrder.  Per unit u (registers 2w, 2w + 1 of owner block qb = u / 8):
     //   0,1  e = 2^t'            2,3  y = 1 + cb e          4,5  P = 1 / y      [6,7  P = 0 on padded rows]
     //   FWD : pack P
-    //   bwd : t = P dP (2 ops), dS = t - P t (2 ops), pack dS, DKDV also packs P
-    constexpr int OPU_BASE = (MODE == FWD) ? 7 : (MODE == DQ ? 11 : 12);
+    //   bwd : g = e P (2 ops), a = P dP (2 ops), dS / cb = g a (2 ops), pack it, DKDV also packs P
+    // 1 - P = cb e P holds without cancellation however close P is to 1, so dS = P (1 - P) dP keeps its
+    // relative accuracy on the saturated tail; the constant cb is applied once, to the finished sums.
+    // e = +inf (score far below the bias) meets P = 0 there: the product must be 0, not NaN.
+    constexpr int OPU_BASE = (MODE == FWD) ? 7 : (MODE == DQ ? 13 : 14);
 
     // One pipeline step on the block (slot, nb) of parity PAR (compile-time nb).  Slots run in program
     // order; a scheduling fence closes each of them.
@@ -518,6 +532,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         constexpr ValuOrder<C::UNITS, OPU, 2, 6> order{};
         constexpr int LEN = DRAIN ? 0 : C::UNITS * OPU;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        float pv[HAS2 ? C::UNITS : 1][2];          // y, then P, of the units in flight (backward only)
 
         static_for<0, SLOTS>([&](auto k_) {
             constexpr int k = decltype(k_)::value;
@@ -548,7 +563,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                     acc0[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         a, __builtin_bit_cast(bf16x8, dsbuf[PAR ^ 1][HAS2 ? qb : 0][half]), acc0[qb][mb], 0, 0, 0);
                     if constexpr (WITH_DB && mb == MB - 1)
-                        accdb[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        accdb[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             ones, __builtin_bit_cast(bf16x8, dsbuf[PAR ^ 1][HAS2 ? qb : 0][half]), accdb[qb], 0, 0, 0);
                 } else {                                // dV^T += dO^T P
                     acc1[MODE == DKDV ? qb : 0][MODE == DKDV ? mb : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -567,25 +582,40 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
                 constexpr int uq = u / 8, w = u % 8, ra = 2 * w, rb = 2 * w + 1;
                 f32x16 &s = sbuf[PAR][uq];
                 f32x16 &dp = dbuf[PAR][HAS2 ? uq : 0];
+                // the forward pass turns the score register into y and P in place; the backward passes keep
+                // e = 2^t' there and carry y, then P, in pv
+                constexpr int pu = HAS2 ? u : 0;
+                auto y_of = [&](auto which) -> float {
+                    if constexpr (HAS2) return pv[pu][decltype(which)::value];
+                    else return s[decltype(which)::value ? rb : ra];
+                };
+                auto set_y = [&](auto which, const float val) {
+                    if constexpr (HAS2) pv[pu][decltype(which)::value] = val;
+                    else s[decltype(which)::value ? rb : ra] = val;
+                };
+                constexpr IntC<0> A_{};
+                constexpr IntC<1> B_{};
                 if constexpr (o == 0) s[ra] = __builtin_amdgcn_exp2f(s[ra]);
                 else if constexpr (o == 1) s[rb] = __builtin_amdgcn_exp2f(s[rb]);
-                else if constexpr (o == 2) s[ra] = __builtin_fmaf(cb, s[ra], 1.0f);
-                else if constexpr (o == 3) s[rb] = __builtin_fmaf(cb, s[rb], 1.0f);
-                else if constexpr (o == 4) s[ra] = __builtin_amdgcn_rcpf(s[ra]);
-                else if constexpr (o == 5) s[rb] = __builtin_amdgcn_rcpf(s[rb]);
-                else if constexpr (MASKED && o == 6) s[ra] = (srow0 + 8 * (ra >> 2) + (ra & 3) < ns) ? s[ra] : 0.f;
-                else if constexpr (MASKED && o == 7) s[rb] = (srow0 + 8 * (rb >> 2) + (rb & 3) < ns) ? s[rb] : 0.f;
+                else if constexpr (o == 2) set_y(A_, __builtin_fmaf(cb, s[ra], 1.0f));
+                else if constexpr (o == 3) set_y(B_, __builtin_fmaf(cb, s[rb], 1.0f));
+                else if constexpr (o == 4) set_y(A_, __builtin_amdgcn_rcpf(y_of(A_)));
+                else if constexpr (o == 5) set_y(B_, __builtin_amdgcn_rcpf(y_of(B_)));
+                else if constexpr (MASKED && o == 6) set_y(A_, (srow0 + 8 * (ra >> 2) + (ra & 3) < ns) ? y_of(A_) : 0.f);
+                else if constexpr (MASKED && o == 7) set_y(B_, (srow0 + 8 * (rb >> 2) + (rb & 3) < ns) ? y_of(B_) : 0.f);
                 else {
                     constexpr int e = o - 6 - MK;     // position in the mode's tail of the unit
                     if constexpr (MODE == FWD) {
                         pbuf[PAR][uq][w / 4][w % 4] = pack_bf16(s[ra], s[rb]);
                     } else {
-                        if constexpr (e == 0) dp[ra] = s[ra] * dp[ra];
-                        else if constexpr (e == 1) dp[rb] = s[rb] * dp[rb];
-                        else if constexpr (e == 2) dp[ra] = __builtin_fmaf(-s[ra], dp[ra], dp[ra]);
-                        else if constexpr (e == 3) dp[rb] = __builtin_fmaf(-s[rb], dp[rb], dp[rb]);
-                        else if constexpr (e == 4) dsbuf[PAR][HAS2 ? uq : 0][w / 4][w % 4] = pack_bf16(dp[ra], dp[rb]);
-                        else pbuf[PAR][uq][w / 4][w % 4] = pack_bf16(s[ra], s[rb]);
+                        if constexpr (e == 0) s[ra] = mul_zero_wins(s[ra], y_of(A_));
+                        else if constexpr (e == 1) s[rb] = mul_zero_wins(s[rb], y_of(B_));
+                        else if constexpr (e == 2) dp[ra] = y_of(A_) * dp[ra];
+                        else if constexpr (e == 3) dp[rb] = y_of(B_) * dp[rb];
+                        else if constexpr (e == 4) dp[ra] = s[ra] * dp[ra];
+                        else if constexpr (e == 5) dp[rb] = s[rb] * dp[rb];
+                        else if constexpr (e == 6) dsbuf[PAR][HAS2 ? uq : 0][w / 4][w % 4] = pack_bf16(dp[ra], dp[rb]);
+                        else pbuf[PAR][uq][w / 4][w % 4] = pack_bf16(y_of(A_), y_of(B_));
                     }
                 }
             });
@@ -719,13 +749,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     }
 
     if constexpr (WITH_DB) {
-        // Row 0 of accdb (register 0 of the lanes with g = 0) holds, per owner row, the sum of dS over all
-        // streamed rows.  Owner rows beyond the valid length carry dO = 0, hence dS = 0.  Fixed-order sums:
-        // lanes by butterfly, waves through LDS, workgroups in a second kernel.
+        // Row 0 of accdb (register 0 of lanes 0..15) holds 16 partial sums that together cover every dS of
+        // this wave.  Owner rows beyond the valid length carry dO = 0, hence dS = 0.  Fixed-order sums: lanes
+        // by butterfly, waves through LDS, workgroups in a second kernel.
         float v = 0.f;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) v += accdb[qb][0];
-        v = (g == 0) ? v : 0.f;
+        v = (lane < 16) ? v : 0.f;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
         __shared__ float s_db[NW];
@@ -735,7 +765,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
             float t = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) t += s_db[w];
-            p.db_part[blockIdx.x] = t;
+            p.db_part[blockIdx.x] = t * cb;                   // the summed values are dS / cb
             p.db_seq[blockIdx.x] = z;
         }
     }
@@ -747,7 +777,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     // whole 16-byte chunks: a quarter of the store instructions and write requests of 8-byte stores.
     using TL_ACC0 = TrLayout<(MODE == FWD) ? C::LM2 : C::LM1>;      // FWD contracts V^T; DQ K^T; DKDV Q^T (acc0), dO^T (acc1)
     using TL_ACC1 = TrLayout<C::LM2>;
-    const float oscale = (MODE == FWD) ? 1.0f : p.scale;            // dQ and dK carry the factor `scale`
+    const float oscale = (MODE == FWD) ? 1.0f : p.scale * cb;       // dQ and dK carry the factor `scale`; their sums are over dS / cb
     auto chunk = [&](const f32x16 &a, const int pr, const float f) {   // columns of q4 = 2 pr + g
         const unsigned e0 = pack_bf16(a[8 * pr + 0] * f, a[8 * pr + 1] * f), e1 = pack_bf16(a[8 * pr + 2] * f, a[8 * pr + 3] * f);
         const unsigned o0 = pack_bf16(a[8 * pr + 4] * f, a[8 * pr + 5] * f), o1 = pack_bf16(a[8 * pr + 6] * f, a[8 * pr + 7] * f);

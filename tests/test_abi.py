@@ -24,6 +24,20 @@ def test_exports_match_header(lib):
         assert hasattr(lib, name), name
 
 
+def test_benchmark_probe_library_is_separate_and_loads():
+    """The matrix-core probe lives in a library and header of its own; the method's library has none of it."""
+    from paper_2604_27124_amd import mfma_probe as M
+    header = open(os.path.join(ROOT, "paper_2604_27124_amd", "csrc", "mfma_probe.h")).read()
+    declared = set(re.findall(r"\b(mfma_probe_\w+)\s*\(", header))
+    assert declared == set(M.EXPORTS)
+    probe = M.load()
+    for name in declared:
+        assert hasattr(probe, name), name
+        assert not hasattr(B.load(), name)
+    assert probe.mfma_probe_launch(None, None, 1, None) == -1           # rejected on the host
+    assert probe.mfma_probe_flops(1) == 512 * 8 * 32 * 2.0 * 32 * 32 * 16
+
+
 def test_version_and_strerror(lib):
     assert B.sigmoid_attn_version() >= 100
     assert B.sigmoid_attn_strerror(0) == "success"
