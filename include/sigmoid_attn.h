@@ -141,6 +141,25 @@ int sigmoid_attn_cross_bwd_dq_dbias(const void *q, const void *k, const void *v,
                                     const float *bias, float scale, int B, int L_q, int L_k, int H, int d,
                                     void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * sigmoid_attn_bwd_dq_dbias for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as sigmoid_attn_bwd_dq_dbias, minus the workspace: the per-workgroup partial sums go
+ * to an array of SIGATTN_STATIC_SCRATCH_BYTES bytes that lives in the library's device image (each GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates and frees nothing.
+ *   limit : B * H * ceil(N_max / 256) * 8 bytes must fit the array (131072 query tiles); beyond that the
+ *           call returns SIGATTN_ERR_TOO_LARGE and enqueues nothing.
+ *   races : every call on one GPU uses that GPU's one array, whatever the stream.  Calls whose kernels
+ *           may overlap on one GPU (different streams, or graphs replayed concurrently) race on it; calls
+ *           on one stream are ordered and safe.  The array keeps the last call's partials; no call relies
+ *           on its contents on entry.
+ * SIGATTN_ERR_LAUNCH is also returned if the array's device address cannot be obtained.
+ */
+#define SIGATTN_STATIC_SCRATCH_BYTES (1 << 20)
+int sigmoid_attn_bwd_dq_dbias_static(const void *q, const void *k, const void *v, const void *d_o, void *dq,
+                                     float *dbias, const int32_t *seqlens, const float *bias, float scale,
+                                     int B, int N_max, int H, int d, void *stream);
+
 /* Scratch bytes sigmoid_attn_bwd needs for this shape (0 on invalid shapes). */
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int N_max, int H, int d);
 

@@ -25,7 +25,8 @@ EXPORTS = ("sigmoid_attn_version", "sigmoid_attn_strerror", "sigmoid_attn_fwd", 
            "sigmoid_attn_bwd_dq", "sigmoid_attn_bwd_dkdv", "sigmoid_attn_bwd_workspace_bytes",
            "sigmoid_attn_cross_fwd", "sigmoid_attn_cross_bwd",
            "sigmoid_attn_bwd_dq_dbias", "sigmoid_attn_bwd_dq_dbias_workspace_bytes",
-           "sigmoid_attn_cross_bwd_dq_dbias", "sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes")
+           "sigmoid_attn_cross_bwd_dq_dbias", "sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes",
+           "sigmoid_attn_bwd_dq_dbias_static")
 
 _lib = None
 
@@ -69,6 +70,8 @@ def load() -> ctypes.CDLL:
         lib.sigmoid_attn_cross_bwd_dq_dbias.restype = ci
         lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         lib.sigmoid_attn_cross_bwd_dq_dbias_workspace_bytes.restype = sz
+        lib.sigmoid_attn_bwd_dq_dbias_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, vp]
+        lib.sigmoid_attn_bwd_dq_dbias_static.restype = ci
         lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
         lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
         _lib = lib
@@ -271,6 +274,25 @@ def sigmoid_attn_bwd_dq_dbias(q, k, v, d_o, seqlens, bias, scale: float, dq=None
                                           dbias.data_ptr(), seqlens.data_ptr(), bias.data_ptr(), float(scale),
                                           B, N, H, d, workspace.data_ptr(),
                                           workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SIGATTN_OK:
+        raise SigAttnError(rc)
+    return dq, dbias
+
+
+def sigmoid_attn_bwd_dq_dbias_static(q, k, v, d_o, seqlens, bias, scale: float, dq, dbias, stream=None):
+    """sigmoid_attn_bwd_dq_dbias without a workspace and without any allocation: the caller passes both
+    outputs (dq like q, dbias float32 [B]); the partial sums go to the library's own static device array."""
+    import torch
+    _check(q, "q")
+    for t, name in ((k, "k"), (v, "v"), (d_o, "d_o"), (dq, "dq")):
+        _check(t, name, q.shape)
+    B, N, H, d = q.shape
+    _check_vec(seqlens, "seqlens", B, torch.int32)
+    _check_vec(bias, "bias", B, torch.float32)
+    _check_vec(dbias, "dbias", B, torch.float32)
+    rc = load().sigmoid_attn_bwd_dq_dbias_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(),
+                                                 dq.data_ptr(), dbias.data_ptr(), seqlens.data_ptr(),
+                                                 bias.data_ptr(), float(scale), B, N, H, d, _stream_ptr(stream))
     if rc != SIGATTN_OK:
         raise SigAttnError(rc)
     return dq, dbias

@@ -4,8 +4,14 @@
 #include "sigmoid_attn.h"
 
 #include <cmath>
+#include <mutex>
 
 using namespace sigattn;
+
+// Scratch of the entry point that allocates nothing: one array per GPU the library runs on, held until the
+// process ends.  In host code this name is only a stand-in; the array's device address comes from
+// hipGetSymbolAddress, once per device (static_scratch() below), and only that pointer is ever handed on.
+static __device__ __align__(256) unsigned char scratch[SIGATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -246,6 +252,42 @@ int sigmoid_attn_bwd_dq_dbias(const void *q, const void *k, const void *v, const
                               void *workspace, size_t workspace_bytes, void *stream) {
     return dq_dbias_impl(q, k, v, d_o, dq, dbias, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d,
                          workspace, workspace_bytes, stream);
+}
+
+// Device address of this GPU's copy of `scratch`: looked up on the first call on each device, with that
+// device current, and kept.  Every GPU holds its own copy of the array at its own address.
+static void *static_scratch() {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static void *ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptr[dev]) {
+        void *a = nullptr;
+        if (hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)) != hipSuccess || !a) return nullptr;
+        ptr[dev] = a;
+    }
+    return ptr[dev];
+}
+
+int sigmoid_attn_bwd_dq_dbias_static(const void *q, const void *k, const void *v, const void *d_o, void *dq,
+                                     float *dbias, const int32_t *seqlens, const float *bias, float scale,
+                                     int B, int N_max, int H, int d, void *stream) {
+    // Argument errors first, on the host, exactly as the workspace form reports them (a non-null, aligned
+    // stand-in of sufficient size takes the place of the workspace for that pass; nothing is launched).
+    if (!q || !k || !v || !d_o || !dq || !dbias || !seqlens || !bias || !std::isfinite(scale)) return SIGATTN_ERR_INVALID_ARG;
+    if (int e = check_shape(B, N_max, H, d)) return e;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+        (reinterpret_cast<uintptr_t>(dbias) & 3u))
+        return SIGATTN_ERR_MISALIGNED;
+    const size_t need = sigmoid_attn_bwd_dq_dbias_workspace_bytes(B, N_max, H, d);
+    if (need > (size_t)SIGATTN_STATIC_SCRATCH_BYTES) return SIGATTN_ERR_TOO_LARGE;   // more query tiles than the array holds
+    void *ws = static_scratch();
+    if (!ws) return SIGATTN_ERR_LAUNCH;
+    // Every workgroup writes its own partial and the second kernel reads exactly those: nothing has to start at zero.
+    return dq_dbias_impl(q, k, v, d_o, dq, dbias, seqlens, seqlens, bias, scale, B, N_max, N_max, H, d,
+                         ws, (size_t)SIGATTN_STATIC_SCRATCH_BYTES, stream);
 }
 
 int sigmoid_attn_cross_bwd_dq_dbias(const void *q, const void *k, const void *v, const void *d_o, void *dq,

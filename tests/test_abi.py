@@ -38,6 +38,19 @@ def test_benchmark_probe_library_is_separate_and_loads():
     assert probe.mfma_probe_flops(1) == 512 * 8 * 32 * 2.0 * 32 * 32 * 16
 
 
+def test_static_scratch_entry_point_rejects_on_the_host(lib):
+    p = 4096                                                  # fake aligned device address: never dereferenced
+    call = lambda **kw: lib.sigmoid_attn_bwd_dq_dbias_static(
+        kw.get("q", p), p, p, kw.get("d_o", p), p, kw.get("dbias", p), p, p, 0.125,
+        kw.get("B", 2), 256, 1, kw.get("d", 64), None)
+    # 131072 query tiles fit the array (8 bytes each in 1 MiB); one more does not
+    assert call(B=131073) == B.SIGATTN_ERR_TOO_LARGE
+    assert call(d_o=None) == B.SIGATTN_ERR_INVALID_ARG
+    assert call(q=p + 2) == B.SIGATTN_ERR_MISALIGNED
+    assert call(dbias=p + 2) == B.SIGATTN_ERR_MISALIGNED
+    assert call(d=96) == B.SIGATTN_ERR_UNSUPPORTED_D
+
+
 def test_version_and_strerror(lib):
     assert B.sigmoid_attn_version() >= 100
     assert B.sigmoid_attn_strerror(0) == "success"
