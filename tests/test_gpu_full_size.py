@@ -58,23 +58,51 @@ def test_jagged_config():
 
 
 def test_long_config_metric_point():
+    # the metric point: three whole (z, h) slices of every sequence, sampled rows on three other heads of
+    # every sequence, exact zeros in all padding, bitwise determinism
     w = W.generate("long", 0)
     dev = Dev(w)
     say("long lengths", w.seqlens.tolist())
+    whole = [(z, h) for z in range(w.B) for h in (1, 6, 10)]
+    say("long whole slices", whole, check_against_oracle(w, slices=whole, dev=dev))
     say("long sampled", sampled_rows_check(w, dev, [(z, h) for z in range(w.B) for h in (0, 5, 11)]))
-    z = int(np.argmin(w.seqlens))
-    say("long whole slice (shortest)", check_against_oracle(w, slices=[(z, 3)], dev=dev))
     first = [to_host(dev.fwd())] + [to_host(t) for t in dev.bwd()]
     again = [to_host(dev.fwd())] + [to_host(t) for t in dev.bwd()]
     for x, y in zip(first, again):
         assert np.array_equal(x, y)
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_long_config_other_seeds(seed):
+    # the other two benchmarked draws of the lengths: one whole slice (shortest sequence) and sampled rows
+    # on two heads of every sequence
+    w = W.generate("long", seed)
+    dev = Dev(w)
+    say("long lengths", seed, w.seqlens.tolist())
+    z = int(np.argmin(w.seqlens))
+    say("long whole slice (shortest)", check_against_oracle(w, slices=[(z, 4)], dev=dev))
+    say("long sampled", sampled_rows_check(w, dev, [(z, h) for z in range(w.B) for h in (2, 9)], seed=seed))
+
+
 def test_wide_head_config():
+    # d = 128 (dK / dV run as the role-swapped forward / dQ pair): one whole slice per sequence, sampled
+    # rows on three more
     w = W.generate("wide", 0)
     dev = Dev(w)
     say("wide lengths", w.seqlens.tolist())
+    say("wide whole slices", check_against_oracle(w, slices=[(0, 3), (1, 12)], dev=dev))
     say("wide sampled", sampled_rows_check(w, dev, [(0, 0), (1, 15), (0, 9)], rows_per_slice=16))
+
+
+@pytest.mark.parametrize("cell", [dict(d=64, H=32, N=512, B=32, pad=0.25), dict(d=64, H=32, N=512, B=32, pad=0.0),
+                                  dict(d=128, H=16, N=2048, B=8, pad=0.25)])
+def test_paper_grid_cells(cell):
+    # cells of the paper's kernel benchmark grid (Sec. 4 "Kernel performance": 16384 tokens per batch, hidden
+    # size 2048, every sequence at (1 - pad) N valid tokens), as the sweep module launches them
+    n = int(round(cell["N"] * (1.0 - cell["pad"])))
+    w = W.make(cell["B"], cell["N"], cell["H"], cell["d"], (n,) * cell["B"], seed=77)
+    slices = [(0, 0), (cell["B"] // 2, cell["H"] // 2), (cell["B"] - 1, cell["H"] - 1), (3, 1)]
+    say("grid cell", cell, check_against_oracle(w, slices=slices))
 
 
 def test_very_long_single_sequence_sampled_rows():

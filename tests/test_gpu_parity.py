@@ -127,6 +127,53 @@ def test_nan_and_inf_in_padded_rows_are_never_read(d):
         assert np.array_equal(x, y)
 
 
+# ---- the 512-row forward instance (two owner blocks per wave), selected when the key side is padded to
+# more than 4096 rows: edge lengths, NaN padding, and agreement with the 256-row instance
+
+WIDE_TILE_N = 4160          # just above 4096: the forward launch takes 512-row owner tiles
+
+
+@pytest.mark.parametrize("seqlens", [(511, 512, 513, 4097), (544, 545, 32, 4160), (0, 1, 1025, 3000)])
+def test_wide_forward_tile_edge_lengths(seqlens):
+    # lengths on and around the 512-row owner tile, a wave whose second 32-row block is wholly padded
+    # (544 = 512 + 32), a single valid row, an empty sequence, the full padded length
+    w = W.make(4, WIDE_TILE_N, 2, 64, seqlens, seed=sum(seqlens) % 1000 + 3)
+    say("512-row forward tile", seqlens, check_against_oracle(w, bwd=False))
+
+
+def test_wide_forward_tile_nan_padding():
+    lens = (513, 4097, 0)
+    w = W.make(3, WIDE_TILE_N, 1, 64, lens, seed=91)
+    ref = to_host(Dev(w).fwd())
+    b = Dev(W.make(3, WIDE_TILE_N, 1, 64, lens, seed=91))
+    for nm, pat in {"q": 0x7FC0, "k": 0x7F80, "v": 0xFF80}.items():
+        raw = getattr(b, nm).view(torch.int16)
+        for z, n in enumerate(lens):
+            raw[z, n:] = pat - 65536 if pat >= 32768 else pat
+    torch.cuda.synchronize()
+    new = to_host(b.fwd())
+    assert np.all(np.isfinite(new)) and np.array_equal(ref, new)
+
+
+def test_forward_tile_shapes_agree():
+    # the same sequences under N_max = 4096 (256-row owner tiles) and N_max = 4160 (512-row owner tiles):
+    # both match the oracle, and they agree with each other under the parity norm (the order of the fp32
+    # sums over key tiles is the same, so in fact bit for bit)
+    lens = (4096, 1300, 513)
+    a = W.make(3, 4096, 2, 64, lens, seed=92)
+    b = W.make(3, WIDE_TILE_N, 2, 64, lens, seed=93)
+    for nm in ("q", "k", "v", "d_o"):
+        getattr(b, nm)[:, :4096] = getattr(a, nm)
+    b.bias[:] = a.bias
+    say("256-row tiles", check_against_oracle(a, bwd=False, slices=[(0, 0), (1, 1), (2, 0)]))
+    say("512-row tiles", check_against_oracle(b, bwd=False, slices=[(0, 0), (1, 1), (2, 0)]))
+    oa, ob = to_host(Dev(a).fwd()), to_host(Dev(b).fwd())
+    for z, n in enumerate(lens):
+        for h in range(2):
+            assert slice_err(ob[z, :n, h], oa[z, :n, h].astype(np.float64)) < FWD_TOL
+    say("tile shapes bitwise equal:", bool(np.array_equal(oa, ob[:, :4096])))
+
+
 def test_more_sequences_than_the_ranked_mapping_holds():
     # B > 256: the work mapping falls back to batch order; every output tile must still be produced once.
     rng = np.random.default_rng(3)
