@@ -52,3 +52,16 @@ def test_entry_module_exposes_build_and_smoke():
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     assert callable(mod.build) and callable(mod.smoke)
+
+
+def test_traffic_lookup_and_confidence_interval():
+    import numpy as np
+    bench = load_bench()
+    # the tracked counter summary is keyed by workload, seed and kernel; anything else has no measurement
+    t = bench.measured_traffic_bytes("long", 0, "bwd_dkdv")
+    assert isinstance(t, int) and 1e8 < t < 1e9
+    assert bench.measured_traffic_bytes("long", 1, "bwd_dkdv") is None
+    assert bench.measured_traffic_bytes("tiny", 0, "fwd") is None
+    m, h = bench.mean_ci99(np.array([1.0, 2.0, 3.0, 4.0]))
+    assert m == 2.5 and abs(h - 2.576 * np.std([1, 2, 3, 4], ddof=1) / 2.0) < 1e-12
+    assert bench.mean_ci99(np.array([5.0])) == (5.0, 0.0)
