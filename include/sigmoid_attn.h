@@ -51,7 +51,8 @@ extern "C" {
 #define SIGATTN_ERR_MISALIGNED (-3)       /* a tensor pointer is not 16-byte aligned                       */
 #define SIGATTN_ERR_WORKSPACE (-4)        /* workspace missing or smaller than ..._workspace_bytes()      */
 #define SIGATTN_ERR_LAUNCH (-5)           /* the HIP runtime refused a launch (see hipGetLastError)       */
-#define SIGATTN_ERR_TOO_LARGE (-6)        /* B*H or the tile count exceeds one grid, or H*d > 2^20        */
+#define SIGATTN_ERR_TOO_LARGE (-6)        /* B*H or the tile count exceeds one grid, H*d > 2^20, or more  */
+                                          /* than 256 sequences padded to more than 262144 rows            */
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int sigmoid_attn_version(void);

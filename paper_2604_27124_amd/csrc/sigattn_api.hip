@@ -21,6 +21,7 @@ int check_shape(int B, int N, int H, int d) {
     if ((long long)B * H > 2147483647LL) return SIGATTN_ERR_TOO_LARGE;     // grid.x limit
     if ((long long)B * N * H * d >= (1LL << 40)) return SIGATTN_ERR_TOO_LARGE;
     if ((long long)H * d > (1LL << 20)) return SIGATTN_ERR_TOO_LARGE;      // 32-bit lane offsets within one streamed tile
+    if (B > MAP_MAX_B && (long long)N > 256LL * MAP_CLASSES) return SIGATTN_ERR_TOO_LARGE;   // tile-count classes of the work mapping
     return SIGATTN_OK;
 }
 

@@ -212,9 +212,28 @@ __device__ __forceinline__ bf16x8 scale_bf16x8(const bf16x8 v, const float f) {
 // Ids are therefore mapped so that the tiles of the LONGEST sequences come first (their cost is
 // proportional to the sequence's valid length), every XCD receives every 8th id of that sorted list, and
 // within one sequence the ids of one XCD are consecutive tiles of the same head; wholly padded tiles,
-// which only write zeros, come last.  Sequences are ranked inside the kernel from
-// seqlens (B <= MAP_MAX_B; larger batches keep batch order), so the host never needs the lengths.
+// which only write zeros, come last.  Sequences are ranked inside the kernel from seqlens, so the host
+// never needs the lengths: up to MAP_MAX_B sequences by their exact length (every thread ranks one
+// sequence against all others in LDS); larger batches by their number of owner tiles (at most
+// MAP_CLASSES of them: the host refuses longer paddings for such batches), with a histogram and
+// block-wide prefix sums (work per thread grows with B / THREADS, not with B).  Ties keep batch order
+// in both forms.
 constexpr int MAP_MAX_B = 256;
+constexpr int MAP_CLASSES = 1024;
+
+// Ids [lo, lo + cnt) are the H * tiles valid ids of one sequence.  Hardware deals consecutive ids round-robin
+// to the 8 XCDs, each with an L2 of its own; the ids of the range that land on one XCD take consecutive
+// tiles of one head (then of the next), so a head's streamed slab is fetched by one or two XCDs only.
+// Returns the position of `id` in that XCD-major order of the range.
+__device__ __forceinline__ int xcd_major_index(int id, int lo, int cnt) {
+    const int idx = id - lo, x = id & 7;
+    int e = 0;                                      // ids of this range on XCDs below x
+    for (int y = 0; y < x; ++y) {
+        const int first = (y - lo) & 7;             // first index of the range that lands on XCD y
+        e += (first < cnt) ? ((cnt - first + 7) >> 3) : 0;
+    }
+    return e + ((idx - ((x - lo) & 7)) >> 3);       // plus the position among the ids on XCD x
+}
 
 template <int BM, int THREADS>
 __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n, int &m0) {
@@ -223,15 +242,16 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
     static_assert((BM & (BM - 1)) == 0, "owner tile rows: a power of two");
     const int T = (p.N + BM - 1) / BM;    // owner tiles per (z, h), padded ones included
     const int id = blockIdx.x;
+    auto len_of = [&](int b) {
+        const int v = p.seqlens[b];
+        return v < 0 ? 0 : (v > p.N ? p.N : v);
+    };
     if (p.B <= MAP_MAX_B) {
         // Id ranges: the valid tiles of every sequence, longest sequence first (ties in batch order), H ids
         // per tile; then the padded tiles in batch order.  One thread per sequence sums, in a single pass over
         // the lengths (uniform LDS reads, no dependent chain), the tiles in front of its own ranges, and the
         // thread whose range holds this workgroup's id publishes the answer.
-        for (int t = threadIdx.x; t < p.B; t += THREADS) {
-            const int v = p.seqlens[t];
-            s_len[t] = v < 0 ? 0 : (v > p.N ? p.N : v);
-        }
+        for (int t = threadIdx.x; t < p.B; t += THREADS) s_len[t] = len_of(t);
         __syncthreads();
         for (int t = threadIdx.x; t < p.B; t += THREADS) {
             const int mine = s_len[t], my_tiles = (mine + BM - 1) / BM;
@@ -244,18 +264,10 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
                 before_padded += (u < t) ? (T - tiles) : 0;
                 all_valid += tiles;
             }
-            {   // valid tiles of sequence t: ids lo .. lo + cnt - 1.  Hardware deals consecutive ids round-robin to
-                // the 8 XCDs, each with an L2 of its own; the ids that land on one XCD take consecutive tiles of
-                // one head (then of the next), so a head's streamed slab is fetched by one or two XCDs only.
+            {   // valid tiles of sequence t: ids lo .. lo + cnt - 1
                 const int lo = before_valid * p.H, cnt = my_tiles * p.H;
                 if (id >= lo && id < lo + cnt) {
-                    const int idx = id - lo, x = id & 7;
-                    int e = 0;                                      // ids of this range on XCDs below x
-                    for (int y = 0; y < x; ++y) {
-                        const int first = (y - lo) & 7;             // first index of the range that lands on XCD y
-                        e += (first < cnt) ? ((cnt - first + 7) >> 3) : 0;
-                    }
-                    e += (idx - ((x - lo) & 7)) >> 3;               // position among the ids on XCD x
+                    const int e = xcd_major_index(id, lo, cnt);
                     s_res[0] = t; s_res[1] = mine; s_res[2] = e / my_tiles; s_res[3] = (e % my_tiles) * BM;
                 }
             }
@@ -271,35 +283,89 @@ __device__ __forceinline__ void map_work(const Params &p, int &z, int &h, int &n
         z = s_res[0]; n = s_res[1]; h = s_res[2]; m0 = s_res[3];
         return;
     }
-    // More sequences than the LDS lists hold: batch order, valid tiles first, then the padded ones.
-    auto len_of = [&](int b) {
-        const int v = p.seqlens[b];
-        return v < 0 ? 0 : (v > p.N ? p.N : v);
-    };
-    int rest = id;
-    bool found = false;
-    z = 0; h = 0; n = 0; m0 = 0;
-    for (int b = 0; b < p.B && !found; ++b) {
-        const int len = len_of(b);
-        const int cnt = ((len + BM - 1) / BM) * p.H;
-        if (rest < cnt) {
-            z = b; n = len; h = rest % p.H; m0 = (rest / p.H) * BM;
-            found = true;
-        } else {
-            rest -= cnt;
+
+    // ---- more sequences than the pairwise ranking holds.  A sequence's class is its number of owner tiles
+    // (class 0 = T tiles, the longest; T <= MAP_CLASSES is the host's check).
+    // Id ranges: classes in ascending order, inside a class the sequences in batch order, H ids per tile;
+    // then the padded tiles in batch order.  All positions are kept in tiles: a sequence whose tiles are
+    // [tb, tb + tiles) of that list owns the ids [H tb, H (tb + tiles)).
+    __shared__ int s_hist[MAP_CLASSES];   // owner tiles per class
+    __shared__ int s_wave[THREADS / 64];  // wave totals of a block-wide prefix sum
+    __shared__ int s_pick[4];             // class holding this id (-1: padded part) | tiles before it | all valid tiles | found
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    auto class_of = [&](int tiles) { return T - tiles; };      // tiles in [1, T]
+    for (int i = tid; i < MAP_CLASSES; i += THREADS) s_hist[i] = 0;
+    if (tid == 0) { s_pick[0] = -1; s_pick[3] = 0; }
+    __syncthreads();
+    for (int b = tid; b < p.B; b += THREADS) {
+        const int tiles = (len_of(b) + BM - 1) / BM;
+        if (tiles > 0) atomicAdd(&s_hist[class_of(tiles)], tiles);
+    }
+    __syncthreads();
+    const int tgt = id / p.H;             // position of this id's tile in the list of all tiles
+    if (wave == 0) {                      // prefix over the classes: each lane sums a run of them, lanes by shuffles
+        constexpr int RUN = MAP_CLASSES / 64;
+        int mine = 0;
+        for (int i = 0; i < RUN; ++i) mine += s_hist[lane * RUN + i];
+        int incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            incl += (lane >= off) ? up : 0;
+        }
+        if (lane == 63) s_pick[2] = incl;
+        int before = incl - mine;
+        if (tgt >= before && tgt < incl) {            // at most one lane
+            int c = lane * RUN;
+            while (tgt >= before + s_hist[c]) { before += s_hist[c]; ++c; }
+            s_pick[0] = c; s_pick[1] = before;
         }
     }
-    for (int b = 0; b < p.B && !found; ++b) {
-        const int len = len_of(b);
-        const int first = (len + BM - 1) / BM;
-        const int cnt = (T - first) * p.H;
-        if (rest < cnt) {
-            z = b; n = len; h = rest % p.H; m0 = (first + rest / p.H) * BM;
-            found = true;
-        } else {
-            rest -= cnt;
+    __syncthreads();
+    const int cls = s_pick[0], all_valid = s_pick[2];
+    const int base = cls >= 0 ? s_pick[1] : all_valid;      // tiles in front of the part that is searched
+    const int rest = tgt - base;                            // position inside that part, in batch order
+    int running = 0;
+    for (int c0 = 0; c0 < p.B; c0 += THREADS) {
+        const int b = c0 + tid;
+        int len = 0, tiles = 0, v = 0;
+        if (b < p.B) {
+            len = len_of(b);
+            tiles = (len + BM - 1) / BM;
+            v = cls >= 0 ? ((tiles > 0 && class_of(tiles) == cls) ? tiles : 0) : T - tiles;
         }
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            incl += (lane >= off) ? up : 0;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int offset = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < THREADS / 64; ++w) {
+            const int t = s_wave[w];
+            offset += (w < wave) ? t : 0;
+            total += t;
+        }
+        const int hi = running + offset + incl, lo_t = hi - v;
+        if (v > 0 && rest >= lo_t && rest < hi) {           // exactly one thread of one chunk
+            const int lo = (base + lo_t) * p.H;             // first id of this sequence's range
+            if (cls >= 0) {
+                const int e = xcd_major_index(id, lo, tiles * p.H);
+                s_res[0] = b; s_res[1] = len; s_res[2] = e / tiles; s_res[3] = (e % tiles) * BM;
+            } else {
+                const int r = id - lo;
+                s_res[0] = b; s_res[1] = len; s_res[2] = r % p.H; s_res[3] = (tiles + r / p.H) * BM;
+            }
+            s_pick[3] = 1;
+        }
+        __syncthreads();
+        if (s_pick[3]) break;
+        running += total;
     }
+    z = s_res[0]; n = s_res[1]; h = s_res[2]; m0 = s_res[3];
 }
 
 template <int MODE, int D, int QB, int NW, int BN, int LD1, int LD2, int OCC, int RING, bool WITH_DB = false>

@@ -80,6 +80,8 @@ def test_fwd_argument_validation(lib):
     assert fwd(k=p + 8) == B.SIGATTN_ERR_MISALIGNED
     assert fwd(o=p + 2) == B.SIGATTN_ERR_MISALIGNED
     assert fwd(B=1 << 20, N=1 << 14, H=1) == B.SIGATTN_ERR_TOO_LARGE  # 2^40 elements per tensor
+    # more than 256 sequences are ranked by tile count, in at most 1024 classes of 256 rows
+    assert fwd(B=257, N=262145, H=1) == B.SIGATTN_ERR_TOO_LARGE
 
 
 def test_bwd_argument_validation(lib):

@@ -174,18 +174,26 @@ def test_forward_tile_shapes_agree():
     say("tile shapes bitwise equal:", bool(np.array_equal(oa, ob[:, :4096])))
 
 
-def test_more_sequences_than_the_ranked_mapping_holds():
-    # B > 256: the work mapping falls back to batch order; every output tile must still be produced once.
-    rng = np.random.default_rng(3)
-    lens = rng.integers(0, 97, size=300)
-    lens[:3] = (96, 0, 1)
-    w = W.make(300, 96, 1, 64, lens, seed=24)
-    say("B=300", check_against_oracle(w, slices=[(z, 0) for z in (0, 1, 2, 57, 150, 299)]))
+@pytest.mark.parametrize("B,N,H", [(300, 96, 1), (2000, 300, 2), (1100, 530, 1)])
+def test_more_sequences_than_the_pairwise_ranking_holds(B, N, H):
+    # B > 256: sequences are ranked by tile count with a histogram and block-wide prefix sums; every owner
+    # tile of every (z, h) must still be produced exactly once (outputs are NaN-poisoned before the call,
+    # so a tile that no workgroup took shows), and sampled slices must match the oracle.
+    rng = np.random.default_rng(3 + B)
+    lens = rng.integers(0, N + 1, size=B)
+    lens[:4] = (N, 0, 1, 257 if N > 257 else N - 1)
+    w = W.make(B, N, H, 64, lens, seed=24)
+    zs = [0, 1, 2, 3, B // 3, B // 2, B - 1, int(np.argmax(lens[4:])) + 4]
     dev = Dev(w)
+    say("large batch", (B, N, H), check_against_oracle(w, slices=[(z, z % H) for z in zs], dev=dev))
     for t in [dev.fwd()] + list(dev.bwd()):
         got = to_host(t)
-        for z in range(300):
-            assert np.all(got[z, int(lens[z]):] == 0.0) and np.all(np.isfinite(got[z]))
+        assert np.all(np.isfinite(got))
+        for z in range(B):
+            assert np.all(got[z, int(lens[z]):] == 0.0)
+        nz = np.any(got != 0.0, axis=(2, 3))                  # [B, N]: rows that hold any non-zero value
+        for z in (4, 5, B // 4, B - 2):
+            assert nz[z, :int(lens[z])].all()                 # (random data: a valid row is never all zero)
 
 
 def test_on_a_side_stream():
