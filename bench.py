@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-ceiling", action="store_true")
+    ap.add_argument("--constant-inputs", action="store_true",
+                    help="diagnostic: every element of Q, K, V, dO is 0.5 (same instruction stream, no toggling in "
+                         "the datapaths); shows how much of the time is the chip's power limit on real data")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
@@ -104,6 +107,9 @@ def main() -> int:
     w = W.generate(args.workload, args.seed)
     dev = lambda a: torch.from_numpy(W.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
     q, k, v, g = dev(w.q), dev(w.k), dev(w.v), dev(w.d_o)
+    if args.constant_inputs:
+        for t in (q, k, v, g):
+            t.fill_(0.5)
     seqlens = torch.from_numpy(w.seqlens).cuda()
     bias = torch.from_numpy(w.bias).cuda()
     o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
@@ -163,7 +169,7 @@ def main() -> int:
         "metric": "fwd+bwd TFLOPS (valid-token FLOPs) + % of bf16 MFMA peak, d=64 N=8192",
         "value": round(tflops, 2), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic" if not args.constant_inputs else "synthetic (diagnostic: all inputs 0.5)",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} N_max={w.N} seed={w.seed}",
                    "seqlens": [int(x) for x in w.seqlens], "qkv_std": w.meta["qkv_std"],
                    "valid_flops_fwd": f_fwd, "valid_flops_bwd": f_bwd},
@@ -183,13 +189,13 @@ def main() -> int:
     if not args.no_mfma_ceiling:
         # the matrix cores alone, same process, same box: nominal rate on constant operands, power-limited
         # sustained rate on random ones (the latter is what any bf16 contraction on real data lives under)
-        from paper_2604_27124_amd import mfma_probe
-        rnd = mfma_probe.tflops("random")
-        cst = mfma_probe.tflops("constant")
+        from paper_2604_27124_amd import machine_probes
+        rnd = machine_probes.mfma_tflops("random")
+        cst = machine_probes.mfma_tflops("constant")
         out["mfma_ceiling"] = {"random_operands_tflops": round(rnd, 1), "constant_operands_tflops": round(cst, 1),
                                "value_over_random_ceiling": round(tflops / rnd, 4),
                                "note": "back-to-back 32x32x16 bf16 MFMAs, nothing else on the CU, ~70-100 ms per run"}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.constant_inputs:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
     return 0

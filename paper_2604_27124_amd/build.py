@@ -10,8 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsigattn.so")
 SOURCES = ["sigattn_api.hip"]
-PROBE_LIB = os.path.join(HERE, "libmfma_probe.so")      # measurement aid for the benchmark, a library of its own
-PROBE_SOURCES = ["mfma_probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libmachine_probes.so")  # measurement aids for the benchmark, a library of their own
+PROBE_SOURCES = ["machine_probes.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -41,7 +41,7 @@ def _compile(lib: str, sources, verbose: bool) -> str:
 
 
 def build_library(verbose: bool = False) -> str:
-    """libsigattn.so (the method) and libmfma_probe.so (the benchmark's matrix-core probe)."""
+    """libsigattn.so (the method) and libmachine_probes.so (the benchmark's measurement aids)."""
     _compile(PROBE_LIB, PROBE_SOURCES, verbose)
     return _compile(LIB, SOURCES, verbose)
 

@@ -26,16 +26,19 @@ def test_exports_match_header(lib):
 
 def test_benchmark_probe_library_is_separate_and_loads():
     """The matrix-core probe lives in a library and header of its own; the method's library has none of it."""
-    from paper_2604_27124_amd import mfma_probe as M
-    header = open(os.path.join(ROOT, "paper_2604_27124_amd", "csrc", "mfma_probe.h")).read()
-    declared = set(re.findall(r"\b(mfma_probe_\w+)\s*\(", header))
+    from paper_2604_27124_amd import machine_probes as M
+    header = open(os.path.join(ROOT, "paper_2604_27124_amd", "csrc", "machine_probes.h")).read()
+    declared = set(re.findall(r"\b(machine_probe_\w+)\s*\(", header))
     assert declared == set(M.EXPORTS)
     probe = M.load()
     for name in declared:
         assert hasattr(probe, name), name
         assert not hasattr(B.load(), name)
-    assert probe.mfma_probe_launch(None, None, 1, None) == -1           # rejected on the host
-    assert probe.mfma_probe_flops(1) == 512 * 8 * 32 * 2.0 * 32 * 32 * 16
+    assert probe.machine_probe_mfma(None, None, 1, None) == -1          # rejected on the host
+    assert probe.machine_probe_atomic(4096, 16, 1, 8, 1, None) == -1    # buffer too small
+    assert probe.machine_probe_loop(4096, 1, 8, None) == -1             # no such component set
+    assert probe.machine_probe_mfma_flops(1) == 512 * 8 * 32 * 2.0 * 32 * 32 * 16
+    assert probe.machine_probe_atomic_updates(2, 3) == 2 * 4 * 3 * 32 * 64
 
 
 def test_static_scratch_entry_point_rejects_on_the_host(lib):
