@@ -378,6 +378,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     constexpr float LOG2E = 1.4426950408889634f;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ float s_db[WITH_DB ? NW : 1];                        // bias gradient: one partial per wave
     bf16_t *y1s = reinterpret_cast<bf16_t *>(smem);                 // [NBUF][BN][LD1]
     bf16_t *y2s = y1s + C::NBUF * BN * LD1;                         // [NBUF][BN][LD2]
 
@@ -392,8 +393,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
     const size_t row_stride = (size_t)p.H * D;
     const size_t slice = ((size_t)z * p.N * p.H + h) * D;           // owner side: element offset of row 0 of (z, h)
     const size_t slice_s = ((size_t)z * p.N_str * p.H + h) * D;     // streamed side
-    int ns = p.seqlens_str[z];                                      // valid rows of the streamed side
-    ns = ns < 0 ? 0 : (ns > p.N_str ? p.N_str : ns);
+    int ns = n;                                                     // valid rows of the streamed side
+    if (p.seqlens_str != p.seqlens || p.N_str != p.N) {             // self-attention: the mapping already has it
+        ns = p.seqlens_str[z];
+        ns = ns < 0 ? 0 : (ns > p.N_str ? p.N_str : ns);
+    }
     ns = __builtin_amdgcn_readfirstlane(ns);
 
     // Wholly padded owner tile, or nothing to stream: write zeros, do nothing else (block-sparse early exit).
@@ -814,6 +818,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         step(F_{}, F_{}, T_{}, IntC<0>{}, slot_next, 0, IntC<-1>{}, 0);
     }
 
+
     if constexpr (WITH_DB) {
         // Row 0 of accdb (register 0 of lanes 0..15) holds 16 partial sums that together cover every dS of
         // this wave.  Owner rows beyond the valid length carry dO = 0, hence dS = 0.  Fixed-order sums: lanes
@@ -824,7 +829,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) sigattn_kernel(const Params p) {
         v = (lane < 16) ? v : 0.f;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-        __shared__ float s_db[NW];
         if (lane == 0) s_db[wave] = v;
         __syncthreads();
         if (tid == 0) {

@@ -61,11 +61,18 @@ def test_tile_barrier_counts_its_reads(kernels):
         for i, ins in enumerate(body):
             if ins != "s_barrier":
                 continue
-            m = re.match(r"s_waitcnt lgkmcnt\((\d+)\)$", body[i - 1])
-            assert m, f"{name}: barrier without an LDS wait in front of it"
+            # the LDS wait that belongs to the barrier: the nearest instruction before it that is not plain
+            # ALU work (the compiler may slip a few such instructions in between; no LDS or scalar-memory
+            # instruction may sit there)
+            w = i - 1
+            while w >= 0 and re.match(r"(v_|s_)(?!waitcnt|load|buffer_load|barrier)", body[w]) and i - w < 8:
+                w -= 1
+            m = re.match(r"s_waitcnt (?:vmcnt\(\d+\) )?lgkmcnt\((\d+)\)$", body[w])
+            assert m, f"{name}: barrier without an LDS wait in front of it ({body[w]!r})"
             allowed = int(m.group(1))
             if allowed == 0:
                 continue                      # a full wait is always safe
+            assert w == i - 1, f"{name}: instructions between a partial LDS wait and its barrier"
             reads, j = 0, i - 2
             while j >= 0 and not body[j].startswith("ds_write"):
                 assert not body[j].startswith(("s_load", "s_buffer_load", "s_barrier")), \
