@@ -16,8 +16,13 @@
  *         machine_probe_atomic_updates(blocks, iters) = 4-byte updates of one launch.
  * loop:   a model of the dK/dV kernel's inner loop on 256 workgroups of 8 waves (two per SIMD): per slot one
  *         MFMA (bit 2 of `components`), one operand fetch from LDS (bit 1) and six VALU instructions of the
- *         backward's mix (bit 0); a barrier every 32 slots.  sink as for mfma.
+ *         backward's mix (bit 0); a barrier every 32 slots.  components = 8: all three, with two 16x16x32
+ *         MFMAs per slot in place of the one 32x32x16 (same FLOPs).  sink as for mfma.
  *         machine_probe_loop_wave_slots_per_simd(iters) = wave-slots each SIMD executes in one launch.
+ * valu:   the backward's vector work for four score elements per iteration (4 exp, 4 rcp, 22 plain instructions)
+ *         on two waves per SIMD, nothing else: arrangement 0 = as the kernels issue them, 1 = all transcendentals
+ *         in one run, 2 = single transcendentals evenly spread, 3 = the plain instructions only, 4 = the
+ *         transcendentals only.  sink as for mfma.
  */
 #ifndef MACHINE_PROBES_H
 #define MACHINE_PROBES_H
@@ -44,6 +49,7 @@ int machine_probe_atomic(void *buffer, size_t bytes, int atomic, int blocks, int
 
 double machine_probe_loop_wave_slots_per_simd(int iters);
 int machine_probe_loop(void *sink, int iters, int components, void *stream);
+int machine_probe_valu(void *sink, int iters, int arrangement, void *stream);
 
 #ifdef __cplusplus
 }

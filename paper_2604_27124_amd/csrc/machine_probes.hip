@@ -22,6 +22,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -112,7 +113,7 @@ __device__ __forceinline__ void probe_static_for(F &&f) {
     }
 }
 
-template <bool VALU, bool LDSR, bool MFMA>
+template <bool VALU, bool LDSR, bool MFMA, bool SMALL = false>
 __global__ void __launch_bounds__(LOOP_THREADS) loop_kernel(float *sink, int iters, float seed) {
     extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
     // four tiles of 64 rows x 72 elements (the kernels' LDS row stride) plus slack, filled with bf16 values of
@@ -132,11 +133,15 @@ __global__ void __launch_bounds__(LOOP_THREADS) loop_kernel(float *sink, int ite
     f32x16 acc[4];
     for (int a = 0; a < 4; ++a)
         for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
-    bf16x8 ring[LOOP_RING], b;
+    f32x4 acs[8];                                    // SMALL: two 16x16x32 MFMAs per slot, same FLOPs
+    for (int a = 0; a < 8; ++a)
+        for (int i = 0; i < 4; ++i) acs[a][i] = 0.f;
+    bf16x8 ring[LOOP_RING], b, b2;
     for (int j = 0; j < 8; ++j) {
         unsigned h = (unsigned)(threadIdx.x * 8 + j) * 2654435761u;
         h ^= h >> 15; h *= 2246822519u;
         b[j] = (__bf16)(((int)(h >> 20) - 2048) * (1.0f / 1024.0f) + seed * 1e-3f);
+        b2[j] = (__bf16)(((int)((h >> 8) & 4095) - 2048) * (1.0f / 1024.0f) + seed * 1e-3f);
     }
 #pragma unroll
     for (int r = 0; r < LOOP_RING; ++r) ring[r] = *reinterpret_cast<const bf16x8 *>(rd + r * 16);
@@ -158,7 +163,10 @@ __global__ void __launch_bounds__(LOOP_THREADS) loop_kernel(float *sink, int ite
     for (int it = 0; it < iters; ++it) {
         probe_static_for<0, LOOP_SLOTS>([&](auto s_) {
             constexpr int s = decltype(s_)::value;
-            if constexpr (MFMA)
+            if constexpr (MFMA && SMALL) {
+                acs[(2 * s) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[s % LOOP_RING], b, acs[(2 * s) & 7], 0, 0, 0);
+                acs[(2 * s + 1) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[s % LOOP_RING], b2, acs[(2 * s + 1) & 7], 0, 0, 0);
+            } else if constexpr (MFMA)
                 acc[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[s % LOOP_RING], b, acc[s & 3], 0, 0, 0);
             else
                 asm volatile("" ::"v"(ring[s % LOOP_RING]));      // the operand is still consumed here
@@ -180,14 +188,67 @@ __global__ void __launch_bounds__(LOOP_THREADS) loop_kernel(float *sink, int ite
     for (int j = 0; j < 8; ++j) s += x[j];
     for (int a = 0; a < 4; ++a)
         for (int i = 0; i < 16; ++i) s += acc[a][i];
+    for (int a = 0; a < 8; ++a)
+        for (int i = 0; i < 4; ++i) s += acs[a][i];
 #pragma unroll
     for (int r = 0; r < LOOP_RING; ++r) s += (float)ring[r][0];
     sink[blockIdx.x * LOOP_THREADS + threadIdx.x] = s;
 }
 
-template <bool VALU, bool LDSR, bool MFMA>
+// ---------------------------------------------------------------------------------------------- valu
+
+// The backward's vector work for four score elements -- 4 exp, 4 rcp, 22 plain instructions of which 3 packs --
+// in different arrangements of the transcendentals among the plain ones; two waves per SIMD, nothing else.
+#define PV_F(i) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[i]) : "v"(ca), "v"(cb));
+#define PV_M(i) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x[i]) : "v"(ca));
+#define PV_E(i) asm volatile("v_exp_f32 %0, %0" : "+v"(x[i]));
+#define PV_R(i) asm volatile("v_rcp_f32 %0, %0" : "+v"(x[i]));
+#define PV_C(i) asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(x[i]) : "v"(cb));
+
+template <int PAT>
+__global__ void __launch_bounds__(LOOP_THREADS) valu_kernel(float *sink, int iters, float seed) {
+    float x[32];
+    for (int j = 0; j < 32; ++j) x[j] = seed + threadIdx.x * 1e-3f + j * 0.01f;
+    const float ca = 0.999f + seed * 1e-6f, cb = 0.5f + seed * 1e-6f;
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (PAT == 0) {   // as the kernels issue them: per two elements  exp exp | fma fma rcp rcp | muls, packs
+            PV_E(0) PV_E(1) PV_F(8) PV_F(9) PV_R(2) PV_R(3) PV_M(10) PV_M(11) PV_M(12) PV_M(13) PV_M(14) PV_M(15) PV_C(16)
+            PV_E(4) PV_E(5) PV_F(17) PV_F(18) PV_R(6) PV_R(7) PV_M(19) PV_M(20) PV_M(21) PV_M(22) PV_M(23) PV_M(24) PV_C(25) PV_C(26)
+        }
+        if constexpr (PAT == 1) {   // all eight transcendentals in one run
+            PV_E(0) PV_E(1) PV_E(4) PV_E(5) PV_R(2) PV_R(3) PV_R(6) PV_R(7) PV_F(8) PV_F(9) PV_M(10) PV_M(11) PV_M(12) PV_M(13) PV_M(14)
+            PV_M(15) PV_C(16) PV_F(17) PV_F(18) PV_M(19) PV_M(20) PV_M(21) PV_M(22) PV_M(23) PV_M(24) PV_C(25) PV_C(26)
+        }
+        if constexpr (PAT == 2) {   // single transcendentals, evenly spread
+            PV_E(0) PV_F(8) PV_F(9) PV_M(10) PV_E(1) PV_M(11) PV_M(12) PV_M(13) PV_R(2) PV_M(14) PV_M(15) PV_C(16) PV_R(3) PV_F(17) PV_F(18)
+            PV_M(19) PV_E(4) PV_M(20) PV_M(21) PV_E(5) PV_M(22) PV_M(23) PV_R(6) PV_M(24) PV_C(25) PV_R(7) PV_C(26)
+        }
+        if constexpr (PAT == 3) {   // the 22 plain instructions only
+            PV_F(8) PV_F(9) PV_M(10) PV_M(11) PV_M(12) PV_M(13) PV_M(14) PV_M(15) PV_C(16) PV_F(17) PV_F(18) PV_M(19) PV_M(20) PV_M(21)
+            PV_M(22) PV_M(23) PV_M(24) PV_C(25) PV_C(26) PV_F(27) PV_F(28) PV_F(29)
+        }
+        if constexpr (PAT == 4) {   // the 8 transcendentals only
+            PV_E(0) PV_E(1) PV_E(4) PV_E(5) PV_R(2) PV_R(3) PV_R(6) PV_R(7)
+        }
+    }
+    float s = 0;
+    for (int j = 0; j < 32; ++j) s += x[j];
+    sink[blockIdx.x * LOOP_THREADS + threadIdx.x] = s;
+}
+
+template <int PAT>
+int launch_valu(float *sink, int iters, hipStream_t stream) {
+    auto kern = valu_kernel<PAT>;      // LDS only to force one workgroup per CU: two waves per SIMD
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            LOOP_LDS_BYTES) != hipSuccess)
+        return MACHINE_PROBE_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(LOOP_BLOCKS), dim3(LOOP_THREADS), LOOP_LDS_BYTES, stream, sink, iters, 0.5f);
+    return hipGetLastError() == hipSuccess ? MACHINE_PROBE_OK : MACHINE_PROBE_ERR_LAUNCH;
+}
+
+template <bool VALU, bool LDSR, bool MFMA, bool SMALL = false>
 int launch_loop(float *sink, int iters, hipStream_t stream) {
-    auto kern = loop_kernel<VALU, LDSR, MFMA>;
+    auto kern = loop_kernel<VALU, LDSR, MFMA, SMALL>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             LOOP_LDS_BYTES) != hipSuccess)
         return MACHINE_PROBE_ERR_LAUNCH;
@@ -235,12 +296,27 @@ double machine_probe_loop_wave_slots_per_simd(int iters) {
     return iters <= 0 ? 0.0 : (double)iters * LOOP_SLOTS * 2.0;
 }
 
-int machine_probe_loop(void *sink, int iters, int components, void *stream) {
-    if (!sink || iters <= 0 || components < 0 || components > 7) return MACHINE_PROBE_ERR_INVALID_ARG;
+int machine_probe_valu(void *sink, int iters, int arrangement, void *stream) {
+    if (!sink || iters <= 0 || arrangement < 0 || arrangement > 4) return MACHINE_PROBE_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(sink) & 3u) return MACHINE_PROBE_ERR_MISALIGNED;
     float *out = static_cast<float *>(sink);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    switch (components) {      // bit 0: VALU, bit 1: LDS reads, bit 2: MFMA
+    switch (arrangement) {
+        case 0: return launch_valu<0>(out, iters, s);
+        case 1: return launch_valu<1>(out, iters, s);
+        case 2: return launch_valu<2>(out, iters, s);
+        case 3: return launch_valu<3>(out, iters, s);
+        default: return launch_valu<4>(out, iters, s);
+    }
+}
+
+int machine_probe_loop(void *sink, int iters, int components, void *stream) {
+    if (!sink || iters <= 0 || components < 0 || components > 8) return MACHINE_PROBE_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(sink) & 3u) return MACHINE_PROBE_ERR_MISALIGNED;
+    float *out = static_cast<float *>(sink);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (components) {      // bit 0: VALU, bit 1: LDS reads, bit 2: MFMA; 8: all three with two 16x16x32 MFMAs per slot
+        case 8: return launch_loop<true, true, true, true>(out, iters, s);
         case 0: return launch_loop<false, false, false>(out, iters, s);
         case 1: return launch_loop<true, false, false>(out, iters, s);
         case 2: return launch_loop<false, true, false>(out, iters, s);

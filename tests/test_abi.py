@@ -36,7 +36,8 @@ def test_benchmark_probe_library_is_separate_and_loads():
         assert not hasattr(B.load(), name)
     assert probe.machine_probe_mfma(None, None, 1, None) == -1          # rejected on the host
     assert probe.machine_probe_atomic(4096, 16, 1, 8, 1, None) == -1    # buffer too small
-    assert probe.machine_probe_loop(4096, 1, 8, None) == -1             # no such component set
+    assert probe.machine_probe_loop(4096, 1, 9, None) == -1             # no such component set
+    assert probe.machine_probe_valu(4096, 1, 5, None) == -1             # no such arrangement
     assert probe.machine_probe_mfma_flops(1) == 512 * 8 * 32 * 2.0 * 32 * 32 * 16
     assert probe.machine_probe_atomic_updates(2, 3) == 2 * 4 * 3 * 32 * 64
 
