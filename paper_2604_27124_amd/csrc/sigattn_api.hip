@@ -132,28 +132,14 @@ static int bwd_impl(const void *q, const void *k, const void *v, const void *d_o
         Params pk = p;
         pk.seqlens = seqlens_k; pk.N = L_k;
         pk.seqlens_str = seqlens_q; pk.N_str = L_q;
-        if (d == 64) {
-            pk.out0 = static_cast<bf16_t *>(dk);
-            pk.out1 = static_cast<bf16_t *>(dv);
-            const int e = launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s);
-            if (e) return e;
-        } else {
-            // At d = 128 the accumulators of dK and dV together do not fit the register file next to the
-            // pipeline, so the two halves of Alg. 3 run as the other two kernels with the roles of queries
-            // and keys exchanged (P is the same number seen from either side):
-            //   dV_j = sum_i P_ij dO_i            is the forward pass with (Q, K, V)     := (K, Q, dO)
-            //   dK_j = scale sum_i dS_ij q_i      is the dQ pass with      (Q, dO, K, V) := (K, V, Q, dO)
-            Params pv = pk;
-            pv.q = p.k; pv.k = p.q; pv.v = p.d_o; pv.d_o = nullptr;
-            pv.out0 = static_cast<bf16_t *>(dv);
-            int e = launch<FWD, 128, 1, 8, 64, 136, 144, 1, 4>(pv, s);
-            if (e) return e;
-            Params pd = pk;
-            pd.q = p.k; pd.d_o = p.v; pd.k = p.q; pd.v = p.d_o;
-            pd.out0 = static_cast<bf16_t *>(dk);
-            e = launch<DQ, 128, 1, 8, 64, 144, 136, 1, 4>(pd, s);
-            if (e) return e;
-        }
+        pk.out0 = static_cast<bf16_t *>(dk);
+        pk.out1 = static_cast<bf16_t *>(dv);
+        // d = 64: eight waves of 32 keys at two waves per SIMD.  d = 128: the fp32 accumulators of dK and dV
+        // (128 registers) fit only with the whole register file of a SIMD for one wave, so four waves of 32
+        // keys, one per SIMD (both streamed tensors are read row-wise and transposed: 288-byte LDS rows).
+        const int e = (d == 64) ? launch<DKDV, 64, 1, 8, 64, 72, 72, 1, 8>(pk, s)
+                                : launch<DKDV, 128, 1, 4, 64, 144, 144, 1, 4>(pk, s);
+        if (e) return e;
     }
     if (want_dq) {           // Alg. 2: dQ (owner = query tile, streamed = keys and values)
         Params pq = p;
