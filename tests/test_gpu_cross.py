@@ -85,3 +85,33 @@ def test_cross_equals_self_when_lengths_agree():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
     for x, y in zip(a, c):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_cross_many_sequences(d):
+    # more than 256 sequences (tile-count ranking of the work mapping) with different lengths on the two
+    # sides: the owner side is ranked, the streamed length is looked up per sequence
+    B = 300
+    rng = np.random.default_rng(7)
+    nq = rng.integers(0, 291, size=B); nk = rng.integers(0, 151, size=B)
+    nq[:3] = (290, 0, 1); nk[:3] = (150, 150, 0)
+    run_case(B, 290, 150, 1, d, nq, nk, seed=5)
+
+
+def test_dq_dbias_many_sequences():
+    # the bias-gradient entry point over more than 256 sequences: one partial per workgroup, summed per sequence
+    B = 300
+    rng = np.random.default_rng(8)
+    lens = rng.integers(0, 301, size=B)
+    w = W.make(B, 300, 2, 64, lens, seed=6)
+    w.v[:] = np.abs(w.v); w.d_o[:] = np.abs(w.d_o)          # every dS >= 0: the sum does not cancel
+    q, k, v, g = to_dev(w.q), to_dev(w.k), to_dev(w.v), to_dev(w.d_o)
+    s, b = torch.from_numpy(w.seqlens).cuda(), torch.from_numpy(w.bias).cuda()
+    dq, db = binding.sigmoid_attn_bwd_dq_dbias(q, k, v, g, s, b, w.scale)
+    dq_only = binding.sigmoid_attn_bwd_dq(q, k, v, g, s, b, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(dq.view(torch.int16), dq_only.view(torch.int16))
+    _, _, _, ref = oracle.cross_bwd(w.q, w.k, w.v, w.d_o, w.seqlens, w.seqlens, w.bias, w.scale)
+    got = db.cpu().numpy().astype(np.float64)
+    assert np.all(got[lens == 0] == 0.0)
+    assert np.all(np.abs(got - ref) <= BWD_TOL * np.abs(ref))
