@@ -59,7 +59,7 @@ const char *sigmoid_attn_strerror(int code) {
         case SIGATTN_ERR_MISALIGNED: return "tensor pointer is not 16-byte aligned";
         case SIGATTN_ERR_WORKSPACE: return "workspace missing or too small";
         case SIGATTN_ERR_LAUNCH: return "HIP kernel launch failed";
-        case SIGATTN_ERR_TOO_LARGE: return "problem too large for one launch";
+        case SIGATTN_ERR_TOO_LARGE: return "problem too large: more workgroups than one launch holds, H*d > 2^20, more than 256 sequences padded beyond 262144 rows, or more query tiles than the static scratch array holds";
         default: return "unknown error code";
     }
 }
